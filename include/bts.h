@@ -1,0 +1,135 @@
+/*
+ * bts -- one parameter-server step of bidirectional Top_K SGD with error feedback
+ * (Algorithm 2 of "Downlink Compression Improves Top_K Sparsification"), simulated on
+ * one MI355X for N workers held as an N x d fp32 batch.
+ *
+ * C ABI.  Unless a parameter is marked "host", every pointer is a DEVICE pointer to
+ * memory owned by the caller; the library never frees or reallocates it.  All work is
+ * queued on the HIP stream given to bts_create and returns without synchronising the
+ * host; results are ready when that stream reaches the end of the queued work.  A
+ * context may be used by one host thread at a time and calls on one context must not
+ * overlap.  The only allocations the library makes are the scratch buffers owned by
+ * the context (made in bts_create, released in bts_destroy).
+ *
+ * Notation (the paper's): N workers, d coordinates, g^q the gradient of worker q,
+ * eps^q its residual, a^q = eps^q + alpha g^q, p_q the worker weights, delta the
+ * server residual, g_t the server's error-compensated aggregate, w the model.
+ *
+ * Top_K(x) keeps the K components of x of largest magnitude and zeroes the rest
+ * (abstract and introduction of the paper).  The paper leaves equal magnitudes and
+ * special values open; this library orders coordinates by the 31-bit pattern of the
+ * fp32 value with the sign cleared (so NaN > Inf > finite > denormal > zero, and +0
+ * ties with -0), larger first, and among equal patterns the LOWER index is kept.  A
+ * message is the K kept (index, value) pairs in ASCENDING index order, values copied
+ * bit for bit; the paper's cost model counts such a message as 2K 32-bit words
+ * (communication section).  The residual x - Top_K(x) is x with +0.0f stored at the
+ * kept positions.  Denormals are never flushed.  Every multiply-add is one fused,
+ * correctly rounded fp32 operation.
+ *
+ * Return value of every call: BTS_OK, or a negative code.  Arguments are checked
+ * before anything is launched; on BTS_EINVAL nothing has been queued.
+ */
+#ifndef BTS_H
+#define BTS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BTS_OK 0
+#define BTS_EINVAL (-1) /* null required pointer, N <= 0, d == 0, d >= 2^32, K > d,        */
+                        /* N > 65535, or a dense buffer (g, eps, delta) not 16-byte aligned */
+#define BTS_ENOMEM (-2) /* scratch allocation failed                                       */
+#define BTS_EHIP (-3)   /* a HIP call failed; see bts_last_hip_error                       */
+
+typedef struct bts_ctx bts_ctx;
+
+/*
+ * Create a context for a fixed problem shape: N workers, d coordinates, K_up kept
+ * coordinates per worker on the uplink, K_dn on the downlink (the paper's experiments
+ * use K_up == K_dn; its communication section treats them separately).  K == 0 and
+ * K == d are legal.  hip_stream is a hipStream_t (host value, borrowed, may be null for
+ * the default stream); every later call on the context queues onto it.  Scratch
+ * (histograms, per-block counts, selection state) is sized here once.
+ */
+int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_dn,
+               void* hip_stream);
+void bts_destroy(bts_ctx* ctx);
+
+/* HIP error code (hipError_t as int) of the last failed HIP call on this context. */
+int bts_last_hip_error(const bts_ctx* ctx);
+
+/*
+ * Worker lines of Algorithm 2, for all N workers at once:
+ *     a^q = eps^q + alpha_in * g^q ;  send Top_K(a^q) ;  eps^q = a^q - Top_K(a^q).
+ * g        N x d row-major fp32, read only (row stride d; d need not be a multiple of 4).
+ * eps      N x d row-major fp32, in: eps_{t-1}, out: eps_t.
+ * alpha_in host scalar, the step size alpha_{t-1} of the paper.
+ * up_idx   N x K_up uint32 out; row q holds worker q's kept coordinates, ascending.
+ * up_val   N x K_up fp32 out; the matching values of a^q.
+ */
+int topk_compress(bts_ctx* ctx, const float* g, float* eps, float alpha_in, uint32_t* up_idx,
+                  float* up_val);
+
+/*
+ * Server aggregation line of Algorithm 2:  g_t = sum_q p_q Top_K(a^q) + delta_{t-1}.
+ * For every coordinate the accumulator starts at delta_{t-1}[i] and the workers that
+ * name i are added in ascending q, one fused multiply-add each, so the result does not
+ * depend on scheduling.  Coordinates no worker names keep their bits.
+ * up_idx, up_val  as written by topk_compress (each row ascending, all indices < d).
+ * p           N fp32 weights (device).
+ * delta       d fp32, in: delta_{t-1}, out: g_t.
+ * union_nnz   nullable; receives the number of distinct coordinates named by the
+ *             uplinks (the "at most K_uplink N non-zero indices" of the paper's
+ *             communication section), one uint32 on the device.
+ */
+int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, const float* p,
+                     float* delta, uint32_t* union_nnz);
+
+/*
+ * Server compression lines of Algorithm 2: send Top_K(g_t), keep
+ * delta_t = g_t - Top_K(g_t).
+ * delta   d fp32, in: g_t, out: delta_t.
+ * dn_idx, dn_val   K_dn pairs out, ascending index.
+ */
+int downlink_topk(bts_ctx* ctx, float* delta, uint32_t* dn_idx, float* dn_val);
+
+/*
+ * Model update line of Algorithm 2 on K received pairs: w[idx] -= alpha_out * val (one
+ * fused multiply-add per pair).  Indices must be distinct and < d.  The paper folds the
+ * step size into a^q and updates with alpha_out = 1.
+ */
+int sparse_sgd_update(bts_ctx* ctx, const uint32_t* idx, const float* val, uint32_t K,
+                      float alpha_out, float* w);
+
+/*
+ * One whole iteration of the loop body of Algorithm 2: topk_compress, sparse_aggregate,
+ * downlink_topk, sparse_sgd_update, queued in that order; results are identical to
+ * making the four calls.  State (eps, delta, w) is updated in place; the uplink and
+ * downlink messages are left in the four output buffers.  union_nnz is nullable.
+ * Paper form: alpha_in = alpha_{t-1}, alpha_out = 1.
+ */
+int bidir_step(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w, const float* p,
+               float alpha_in, float alpha_out, uint32_t* up_idx, float* up_val,
+               uint32_t* dn_idx, float* dn_val, uint32_t* union_nnz);
+
+/*
+ * Timing of the dominant kernel (the dense pass over g and eps in topk_compress).  While
+ * enabled, the library brackets that kernel with HIP events on the context's stream.
+ * bts_profile_read synchronises those events and returns the summed kernel time in
+ * milliseconds and the number of launches since the last read (both host pointers).
+ */
+int bts_profile_enable(bts_ctx* ctx, int on);
+int bts_profile_read(bts_ctx* ctx, double* ms_total, uint64_t* launches);
+
+/* Path taken by the last topk_compress / downlink_topk on this context, for tests and
+ * reports: a host-synchronous read of per-row flags.  rows_fast + rows_dense == rows.
+ * which: 0 = uplink, 1 = downlink. */
+int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_dense);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BTS_H */

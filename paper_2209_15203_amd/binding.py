@@ -1,0 +1,154 @@
+"""ctypes binding of libbts.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbts.so")
+
+EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
+           "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
+           "bts_profile_enable", "bts_profile_read", "bts_last_path"]
+
+_lib = None
+
+
+class BtsError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built HIP library.  It is never built here: run ``__graft_entry__.build()``
+    (or ``python -m paper_2209_15203_amd.build``) first."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise BtsError(f"{_LIB_PATH} is missing: build the HIP library first "
+                       f"(python -m paper_2209_15203_amd.build); there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    vp, u32, u64, i32, f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32, C.c_float
+    lib.bts_create.argtypes = [C.POINTER(vp), i32, u64, u32, u32, vp]
+    lib.bts_destroy.argtypes = [vp]
+    lib.bts_destroy.restype = None
+    lib.bts_last_hip_error.argtypes = [vp]
+    lib.topk_compress.argtypes = [vp, vp, vp, f32, vp, vp]
+    lib.sparse_aggregate.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.downlink_topk.argtypes = [vp, vp, vp, vp]
+    lib.sparse_sgd_update.argtypes = [vp, vp, vp, u32, f32, vp]
+    lib.bidir_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
+    lib.bts_profile_enable.argtypes = [vp, C.c_int]
+    lib.bts_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64)]
+    lib.bts_last_path.argtypes = [vp, C.c_int, C.POINTER(u32), C.POINTER(u32)]
+    for name in EXPORTS:
+        if name != "bts_destroy":
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+_CODES = {-1: "BTS_EINVAL", -2: "BTS_ENOMEM", -3: "BTS_EHIP"}
+
+
+def _ptr(t: Optional[torch.Tensor], dtype, name: str):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+    return C.c_void_p(t.data_ptr())
+
+
+class BtsContext:
+    """Owns a ``bts_ctx`` bound to the current torch HIP stream."""
+
+    def __init__(self, N: int, d: int, K_up: int, K_dn: int,
+                 stream: Optional[torch.cuda.Stream] = None):
+        self._lib = load_library()
+        self.N, self.d, self.K_up, self.K_dn = N, d, K_up, K_dn
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = C.c_void_p()
+        rc = self._lib.bts_create(C.byref(h), N, d, K_up, K_dn, C.c_void_p(self.stream.cuda_stream))
+        if rc != 0:
+            raise BtsError(f"bts_create failed: {_CODES.get(rc, rc)}")
+        self._h = h
+
+    def check(self, rc: int, what: str) -> None:
+        if rc != 0:
+            hip = self._lib.bts_last_hip_error(self._h) if rc == -3 else 0
+            raise BtsError(f"{what} failed: {_CODES.get(rc, rc)} (hip error {hip})")
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.bts_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # profiling of the dominant kernel
+    def profile_enable(self, on: bool) -> None:
+        self.check(self._lib.bts_profile_enable(self._h, int(on)), "bts_profile_enable")
+
+    def profile_read(self) -> Tuple[float, int]:
+        ms, n = C.c_double(0.0), C.c_uint64(0)
+        self.check(self._lib.bts_profile_read(self._h, C.byref(ms), C.byref(n)), "bts_profile_read")
+        return ms.value, n.value
+
+    def last_path(self, which: int) -> Tuple[int, int]:
+        a, b = C.c_uint32(0), C.c_uint32(0)
+        self.check(self._lib.bts_last_path(self._h, which, C.byref(a), C.byref(b)), "bts_last_path")
+        return a.value, b.value
+
+
+F32, U32 = torch.float32, torch.int32   # uint32 words travel in int32 tensors
+
+
+def topk_compress(ctx: BtsContext, g, eps, alpha_in: float, up_idx, up_val) -> None:
+    ctx.check(ctx._lib.topk_compress(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"), alpha_in,
+                                     _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val")),
+              "topk_compress")
+
+
+def sparse_aggregate(ctx: BtsContext, up_idx, up_val, p, delta, union_nnz=None) -> None:
+    ctx.check(ctx._lib.sparse_aggregate(ctx._h, _ptr(up_idx, U32, "up_idx"),
+                                        _ptr(up_val, F32, "up_val"), _ptr(p, F32, "p"),
+                                        _ptr(delta, F32, "delta"),
+                                        _ptr(union_nnz, U32, "union_nnz")), "sparse_aggregate")
+
+
+def downlink_topk(ctx: BtsContext, delta, dn_idx, dn_val) -> None:
+    ctx.check(ctx._lib.downlink_topk(ctx._h, _ptr(delta, F32, "delta"),
+                                     _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val")),
+              "downlink_topk")
+
+
+def sparse_sgd_update(ctx: BtsContext, idx, val, K: int, alpha_out: float, w) -> None:
+    ctx.check(ctx._lib.sparse_sgd_update(ctx._h, _ptr(idx, U32, "idx"), _ptr(val, F32, "val"), K,
+                                         alpha_out, _ptr(w, F32, "w")), "sparse_sgd_update")
+
+
+def bidir_step(ctx: BtsContext, g, eps, delta, w, p, alpha_in: float, alpha_out: float,
+               up_idx, up_val, dn_idx, dn_val, union_nnz=None) -> None:
+    ctx.check(ctx._lib.bidir_step(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"),
+                                  _ptr(delta, F32, "delta"), _ptr(w, F32, "w"), _ptr(p, F32, "p"),
+                                  alpha_in, alpha_out, _ptr(up_idx, U32, "up_idx"),
+                                  _ptr(up_val, F32, "up_val"), _ptr(dn_idx, U32, "dn_idx"),
+                                  _ptr(dn_val, F32, "dn_val"),
+                                  _ptr(union_nnz, U32, "union_nnz")), "bidir_step")

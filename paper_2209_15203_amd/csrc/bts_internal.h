@@ -1,0 +1,58 @@
+// Internal declarations shared by the HIP translation units of libbts (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bts {
+
+constexpr int kWave = 64;                 // CDNA wavefront
+constexpr int kBlock = 256;               // threads per workgroup in the dense passes
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kUnroll = 8;                // float4 loads in flight per lane and array
+// A wave owns kWaveChunk consecutive coordinates (absolute, 16-byte aligned offsets).
+constexpr uint32_t kWaveChunk = kWave * 4 * kUnroll;   // 2048
+constexpr int kBins0 = 2048;              // first digit: key bits 30..20
+constexpr int kBinsLo = 1024;             // second and third digit: bits 19..10, 9..0
+
+// Per-row state of the exact radix select on the 31-bit magnitude key.
+struct SelState {
+  uint32_t prefix;   // key bits fixed so far (right aligned)
+  uint32_t k_rem;    // how many of the wanted K lie at or below the current bin
+  uint32_t T;        // exact K-th largest key (valid after the third digit)
+  uint32_t r;        // how many coordinates with key == T are kept (lowest indices first)
+};
+
+// Rows that a gated kernel must process (null pointer = all rows).
+using RowMask = const uint32_t*;
+
+struct DenseScratch {
+  uint32_t* hist;     // rows x kBins0
+  SelState* state;    // rows
+  uint32_t* cnt_gt;   // rows x nwc: per wave-chunk count of key > T, then exclusive offsets
+  uint32_t* cnt_eq;   // rows x nwc: same for key == T
+  uint32_t nwc;       // wave-chunks per row (upper bound, same for every row)
+};
+
+// ---- dense exact select (handles any input, any K in 1..d) ----------------------------
+// x: rows x d (row stride d).  If g != nullptr the first pass computes
+// x = fma(alpha, g, x) and stores it (the worker's error compensation) while it builds
+// the first histogram.  On return (stream order) idx/val hold K pairs per row in
+// ascending index order and x holds +0 at those positions.
+hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
+                        uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
+                        float* out_val, RowMask need, bool first_pass_done,
+                        hipEvent_t ev0, hipEvent_t ev1);
+
+// x = fma(alpha, g, x) over rows x d and nothing else (K == 0).
+hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
+                     float alpha, hipEvent_t ev0, hipEvent_t ev1);
+
+// ---- server side ------------------------------------------------------------------------
+hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
+                     uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz);
+hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint32_t K,
+                      float alpha_out, float* w, uint64_t d);
+hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v);
+
+}  // namespace bts

@@ -1,0 +1,301 @@
+// Dense exact Top_K select: a three-digit (11 + 10 + 10 bit) radix select on the 31-bit
+// magnitude key with LDS histograms, followed by an ordered emission that needs no
+// atomics for placement: per-wave-chunk counts of (key > T) and (key == T), an exclusive
+// scan over the chunks of a row, and in-wave ballot/popcount prefix sums.  Ties at the
+// threshold go to the lowest indices.  Works for every input and every K in 1..d; it is
+// the reference path of the library and the fallback of the speculative single-pass path.
+//
+// Implements the Top_K operator used on the worker and server compression lines of
+// Algorithm 2 (a^q -> Top_K(a^q), eps^q = a^q - Top_K(a^q); g_t -> Top_K(g_t),
+// delta_t = g_t - Top_K(g_t)); the first pass can also fuse the worker's error
+// compensation a^q = eps^q + alpha g^q.
+
+#include "bts_device.h"
+
+namespace bts {
+
+namespace {
+
+__device__ __forceinline__ bool row_needed(RowMask need, uint32_t row) {
+  return need == nullptr || need[row] != 0;
+}
+
+// Histogram of one digit of the key over every coordinate of the row whose higher digits
+// match the prefix found so far.
+template <int DIGIT, bool FMA>
+__global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
+                                                 float* __restrict__ x, uint64_t d, float alpha,
+                                                 const SelState* __restrict__ st,
+                                                 uint32_t* __restrict__ hist, RowMask need) {
+  constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
+  __shared__ uint32_t sh[NB];
+  const uint32_t row = blockIdx.y;
+  if (!row_needed(need, row)) return;
+  for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
+  __syncthreads();
+  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  const ChunkGeom c = wave_chunk(d, row, wc);
+  const uint32_t prefix = DIGIT == 0 ? 0u : st[row].prefix;
+  if (c.active) {
+    visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t, const float (&v)[4], uint32_t mask) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (mask & (1u << j)) {
+          const uint32_t key = key_of(v[j]);
+          if (DIGIT == 0) {
+            atomicAdd(&sh[key >> 20], 1u);
+          } else if (DIGIT == 1) {
+            if ((key >> 20) == prefix) atomicAdd(&sh[(key >> 10) & 1023u], 1u);
+          } else {
+            if ((key >> 10) == prefix) atomicAdd(&sh[key & 1023u], 1u);
+          }
+        }
+      }
+    });
+  }
+  __syncthreads();
+  uint32_t* h = hist + (uint64_t)row * kBins0;
+  for (int i = threadIdx.x; i < NB; i += kBlock) {
+    const uint32_t v = sh[i];
+    if (v) atomicAdd(&h[i], v);
+  }
+}
+
+// Walk the histogram of one digit from the top bin down and fix that digit of the K-th
+// largest key.  One block per row.  Leaves the histogram zeroed for the next digit.
+template <int DIGIT>
+__global__ __launch_bounds__(kBlock) void k_scan_digit(uint32_t* __restrict__ hist,
+                                                       SelState* __restrict__ st, uint32_t K,
+                                                       RowMask need) {
+  constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
+  constexpr int BPT = NB / kBlock;
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  const uint32_t row = blockIdx.x;
+  if (!row_needed(need, row)) return;
+  uint32_t* h = hist + (uint64_t)row * kBins0;
+  const uint32_t k_rem = DIGIT == 0 ? K : st[row].k_rem;
+  const int top = NB - 1 - (int)threadIdx.x * BPT;   // this thread's highest bin
+  uint32_t c[BPT];
+  uint32_t s = 0;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) {
+    c[i] = h[top - i];
+    s += c[i];
+    h[top - i] = 0;
+  }
+  uint32_t total;
+  const uint32_t excl = block_exclusive_scan(s, lds, &total);   // count in higher bins
+  if (excl < k_rem && k_rem <= excl + s) {                       // exactly one thread
+    uint32_t acc = excl;
+    int bin = top;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) {
+      if (acc + c[i] >= k_rem) {
+        bin = top - i;
+        break;
+      }
+      acc += c[i];
+    }
+    const uint32_t prefix = DIGIT == 0 ? (uint32_t)bin : ((st[row].prefix << 10) | (uint32_t)bin);
+    st[row].prefix = prefix;
+    st[row].k_rem = k_rem - acc;
+    if (DIGIT == 2) {
+      st[row].T = prefix;
+      st[row].r = k_rem - acc;
+    }
+  }
+}
+
+// Per wave-chunk: how many coordinates lie strictly above the threshold key, how many
+// on it.
+__global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, uint64_t d,
+                                                  const SelState* __restrict__ st,
+                                                  uint32_t* __restrict__ cnt_gt,
+                                                  uint32_t* __restrict__ cnt_eq, uint32_t nwc,
+                                                  RowMask need) {
+  const uint32_t row = blockIdx.y;
+  if (!row_needed(need, row)) return;
+  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (wc >= nwc) return;
+  const ChunkGeom c = wave_chunk(d, row, wc);
+  const uint32_t T = st[row].T;
+  uint32_t gt = 0, eq = 0;
+  if (c.active) {
+    visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f,
+                       [&](uint64_t, const float (&v)[4], uint32_t mask) {
+#pragma unroll
+                         for (int j = 0; j < 4; ++j) {
+                           const uint32_t key = key_of(v[j]);
+                           const bool in = mask & (1u << j);
+                           gt += (in && key > T) ? 1u : 0u;
+                           eq += (in && key == T) ? 1u : 0u;
+                         }
+                       });
+  }
+  gt = wave_sum(gt);
+  eq = wave_sum(eq);
+  if (lane_id() == 0) {
+    cnt_gt[(uint64_t)row * nwc + wc] = gt;
+    cnt_eq[(uint64_t)row * nwc + wc] = eq;
+  }
+}
+
+// Exclusive scan of the per-chunk counts of one row, in place.  One block of 1024 threads
+// per row; thread t owns a contiguous slice of the chunks.
+__global__ __launch_bounds__(1024) void k_scan_chunks(uint32_t* __restrict__ cnt_gt,
+                                                      uint32_t* __restrict__ cnt_eq,
+                                                      uint32_t nwc, RowMask need) {
+  __shared__ uint32_t lds[1024 / kWave + 1];
+  const uint32_t row = blockIdx.x;
+  if (!row_needed(need, row)) return;
+  const uint32_t per = (nwc + blockDim.x - 1) / blockDim.x;
+  const uint32_t b = threadIdx.x * per;
+  const uint32_t e = min(b + per, nwc);
+#pragma unroll 1
+  for (int which = 0; which < 2; ++which) {
+    uint32_t* a = (which == 0 ? cnt_gt : cnt_eq) + (uint64_t)row * nwc;
+    uint32_t s = 0;
+    for (uint32_t i = b; i < e; ++i) s += a[i];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(s, lds, &total);
+    for (uint32_t i = b; i < e; ++i) {
+      const uint32_t t = a[i];
+      a[i] = run;
+      run += t;
+    }
+  }
+}
+
+// Ordered emission.  Every wave re-reads its chunk, ranks its kept coordinates with
+// ballots and writes (index, value) to the row's message at
+//     #kept before it = #(key > T) before it + min(#(key == T) before it, r),
+// then stores +0 over the kept coordinate (the residual).
+__global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t d, uint32_t K,
+                                                 const SelState* __restrict__ st,
+                                                 const uint32_t* __restrict__ off_gt,
+                                                 const uint32_t* __restrict__ off_eq,
+                                                 uint32_t nwc, uint32_t* __restrict__ out_idx,
+                                                 float* __restrict__ out_val, RowMask need) {
+  const uint32_t row = blockIdx.y;
+  if (!row_needed(need, row)) return;
+  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (wc >= nwc) return;
+  const ChunkGeom c = wave_chunk(d, row, wc);
+  if (!c.active) return;
+  const uint32_t T = st[row].T, r = st[row].r;
+  uint32_t run_gt = off_gt[(uint64_t)row * nwc + wc];   // wave-uniform running counts
+  uint32_t run_eq = off_eq[(uint64_t)row * nwc + wc];
+  uint32_t* oi = out_idx + (uint64_t)row * K;
+  float* ov = out_val + (uint64_t)row * K;
+  visit_chunk<false>(nullptr, x, c, 0.0f, [&](uint64_t e, const float (&v)[4], uint32_t mask) {
+    uint32_t fgt = 0, feq = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t key = key_of(v[j]);
+      const bool in = mask & (1u << j);
+      fgt |= (in && key > T) ? (1u << j) : 0u;
+      feq |= (in && key == T) ? (1u << j) : 0u;
+    }
+    if (__ballot(fgt | feq) == 0) return;     // nothing near the threshold in this slice
+    uint32_t tot_gt, tot_eq;
+    uint32_t my_gt = run_gt + wave_exclusive_small(__popc(fgt), &tot_gt);
+    uint32_t my_eq = run_eq + wave_exclusive_small(__popc(feq), &tot_eq);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool is_gt = fgt & (1u << j), is_eq = feq & (1u << j);
+      if (is_gt || (is_eq && my_eq < r)) {
+        const uint32_t pos = my_gt + min(my_eq, r);
+        if (pos < K) {
+          oi[pos] = (uint32_t)(e + j - c.lo);
+          ov[pos] = v[j];
+          x[e + j] = 0.0f;
+        }
+      }
+      my_gt += is_gt ? 1u : 0u;
+      my_eq += is_eq ? 1u : 0u;
+    }
+    run_gt += tot_gt;
+    run_eq += tot_eq;
+  });
+}
+
+// x = fma(alpha, g, x) with no selection (K == 0).
+__global__ __launch_bounds__(kBlock) void k_axpy(const float* __restrict__ g,
+                                                 float* __restrict__ x, uint64_t d,
+                                                 float alpha) {
+  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  const ChunkGeom c = wave_chunk(d, blockIdx.y, wc);
+  if (c.active) visit_chunk<true>(g, x, c, alpha, [](uint64_t, const float (&)[4], uint32_t) {});
+}
+
+__global__ void k_fill(uint32_t* p, uint64_t n, uint32_t v) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+#define BTS_LAUNCH_CHECK()                       \
+  do {                                           \
+    hipError_t e_ = hipGetLastError();           \
+    if (e_ != hipSuccess) return e_;             \
+  } while (0)
+
+}  // namespace
+
+hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v) {
+  if (n == 0) return hipSuccess;
+  k_fill<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
+                     float alpha, hipEvent_t ev0, hipEvent_t ev1) {
+  const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
+  dim3 grid((nwc + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  if (ev0) (void)hipEventRecord(ev0, s);
+  k_axpy<<<grid, dim3(kBlock), 0, s>>>(g, x, d, alpha);
+  BTS_LAUNCH_CHECK();
+  if (ev1) (void)hipEventRecord(ev1, s);
+  return hipSuccess;
+}
+
+hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
+                        uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
+                        float* out_val, RowMask need, bool first_pass_done,
+                        hipEvent_t ev0, hipEvent_t ev1) {
+  const uint32_t nwc = sc.nwc;
+  const dim3 grid((nwc + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  const dim3 block(kBlock);
+  hipError_t e = fill_u32(s, sc.hist, (uint64_t)rows * kBins0, 0);
+  if (e != hipSuccess) return e;
+
+  const bool fuse = (g != nullptr) && !first_pass_done;
+  if (fuse) {
+    if (ev0) (void)hipEventRecord(ev0, s);
+    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, sc.state, sc.hist, need);
+    BTS_LAUNCH_CHECK();
+    if (ev1) (void)hipEventRecord(ev1, s);
+  } else {
+    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, need);
+    BTS_LAUNCH_CHECK();
+  }
+  k_scan_digit<0><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
+  BTS_LAUNCH_CHECK();
+  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, need);
+  BTS_LAUNCH_CHECK();
+  k_scan_digit<1><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
+  BTS_LAUNCH_CHECK();
+  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, need);
+  BTS_LAUNCH_CHECK();
+  k_scan_digit<2><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
+  BTS_LAUNCH_CHECK();
+  k_count<<<grid, block, 0, s>>>(x, d, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need);
+  BTS_LAUNCH_CHECK();
+  k_scan_chunks<<<dim3(rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, need);
+  BTS_LAUNCH_CHECK();
+  k_emit<<<grid, block, 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, out_idx, out_val,
+                                need);
+  BTS_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+}  // namespace bts

@@ -1,0 +1,62 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad shapes before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bts.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:int|void|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+    assert len(names) >= 10
+    return names
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2209_15203_amd import binding
+    if not os.path.exists(binding.lib_path()):
+        from paper_2209_15203_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2209_15203_amd import binding
+    names = declared_symbols()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(names) == sorted(binding.EXPORTS)
+
+
+def test_create_rejects_bad_shapes_without_a_gpu(lib):
+    h = C.c_void_p()
+    bad = [(0, 100, 1, 1), (-3, 100, 1, 1), (4, 0, 0, 0), (4, 1 << 32, 1, 1), (4, 100, 101, 1),
+           (4, 100, 1, 101), (70000, 100, 1, 1)]
+    for N, d, ku, kd in bad:
+        assert lib.bts_create(C.byref(h), N, d, ku, kd, None) == -1
+        assert not h.value
+    assert lib.bts_create(None, 4, 100, 1, 1, None) == -1
+
+
+def test_null_context_is_rejected(lib):
+    assert lib.topk_compress(None, None, None, 0.0, None, None) == -1
+    assert lib.sparse_aggregate(None, None, None, None, None, None) == -1
+    assert lib.downlink_topk(None, None, None, None) == -1
+    assert lib.sparse_sgd_update(None, None, None, 0, 0.0, None) == -1
+    assert lib.bidir_step(None, None, None, None, None, None, 0.0, 0.0, None, None, None, None,
+                          None) == -1
+    lib.bts_destroy(None)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2209_15203_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libbts.so")
+    with pytest.raises(binding.BtsError):
+        binding.load_library()

@@ -1,0 +1,265 @@
+"""GPU parity tests: every entry point of the C ABI against the CPU oracle, bit for bit
+(0 ulp on every fp32 output, exact on every index), on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import _gpu_util
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return _gpu_util
+
+
+def tied_rows(rng, N, d, levels=3):
+    """Rows whose magnitudes take only a few values, random signs: boundary ties everywhere."""
+    mag = rng.integers(1, levels + 1, size=(N, d)).astype(np.float32)
+    return mag * rng.choice(np.array([-1.0, 1.0], np.float32), size=(N, d))
+
+
+SHAPES = [
+    # N, d, K   (ragged rows: d % 4 != 0 puts rows off 16-byte alignment; d below one chunk;
+    #            several chunks and a tail; K = 1, K = d)
+    (1, 1, 1), (3, 5, 2), (2, 63, 7), (4, 1000, 10), (3, 2049, 33), (5, 4099, 4099),
+    (2, 10007, 1), (7, 30011, 301), (4, 65536, 66), (3, 100003, 1001), (2, 262147, 5000),
+]
+
+
+@pytest.mark.parametrize("N,d,K", SHAPES)
+@pytest.mark.parametrize("kind", ["normal", "ties"])
+def test_topk_compress(G, oracle, N, d, K, kind):
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(N * 1000003 + d * 7 + K)
+    g = rng.standard_normal((N, d)).astype(np.float32) if kind == "normal" else tied_rows(rng, N, d)
+    eps0 = (rng.standard_normal((N, d)) * 0.5).astype(np.float32) if kind == "normal" \
+        else np.zeros((N, d), np.float32)
+    alpha = 0.37 if kind == "normal" else 1.0
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    tg, te = torch.from_numpy(g).to(D), torch.from_numpy(eps0).to(D)
+    ui = torch.full((N, K), -1, dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+    bts.topk_compress(ctx, tg, te, alpha, ui, uv)
+    torch.cuda.synchronize()
+    h_eps = eps0.copy()
+    want_i, want_v = oracle.worker_stage(g, h_eps, alpha, K)
+    G.assert_same_bits(ui, want_i, "up_idx")
+    G.assert_same_bits(uv, want_v, "up_val")
+    G.assert_same_bits(te, h_eps, "eps")
+    G.assert_same_bits(tg, g, "g must not be modified")
+
+
+def test_k_zero_is_plain_error_accumulation(G, oracle):
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(1)
+    N, d = 3, 5001
+    g = rng.standard_normal((N, d)).astype(np.float32)
+    e = rng.standard_normal((N, d)).astype(np.float32)
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, 0, 0)
+    tg, te = torch.from_numpy(g).to(D), torch.from_numpy(e).to(D)
+    bts.topk_compress(ctx, tg, te, 0.01, None, None)
+    torch.cuda.synchronize()
+    h = e.copy()
+    oracle.worker_stage(g, h, 0.01, 0)
+    G.assert_same_bits(te, h, "eps")
+
+
+def test_threshold_run_spanning_many_workgroups(G, oracle):
+    """Three distinct magnitudes at a realistic d; the K-th largest falls inside a run of
+    equal keys that spans hundreds of workgroups, so the lowest-index rule decides."""
+    import paper_2209_15203_amd as bts
+    d = 3_000_001
+    x = np.empty(d, np.float32)
+    x[0::3], x[1::3], x[2::3] = 1.0, -2.0, 3.0
+    n3, n2 = len(x[2::3]), len(x[1::3])
+    D = G.dev()
+    for K in (n3 + n2 + 123_457, n3 - 5, n3 + 1, 17):
+        ctx = bts.BtsContext(1, d, K, K)
+        t = torch.from_numpy(x.copy()).to(D)
+        oi = torch.zeros(K, dtype=torch.int32, device=D)
+        ov = torch.zeros(K, dtype=torch.float32, device=D)
+        bts.downlink_topk(ctx, t, oi, ov)
+        torch.cuda.synchronize()
+        h = x.copy()
+        wi, wv = oracle.downlink(h, K)
+        G.assert_same_bits(oi, wi, f"K={K} idx")
+        G.assert_same_bits(ov, wv, f"K={K} val")
+        G.assert_same_bits(t, h, f"K={K} residual")
+
+
+def test_special_values_are_ordered_by_magnitude_bits(G, oracle):
+    """NaN > Inf > finite > denormal > zero, +0 ties with -0, values copied bit for bit."""
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(2)
+    d = 9001
+    x = rng.standard_normal(d).astype(np.float32)
+    xb = x.view(np.uint32)
+    xb[10] = 0x7FC00001          # NaN with payload
+    xb[20] = 0xFFC00000          # negative NaN
+    xb[30] = 0x7F800000          # +Inf
+    xb[40] = 0xFF800000          # -Inf
+    xb[50:60] = 0x00000003       # denormals
+    xb[60:70] = 0x80000003
+    xb[100:200] = 0x80000000     # -0
+    xb[200:300] = 0x00000000     # +0
+    x[300:4000] = 0.0
+    D = G.dev()
+    for K in (1, 2, 3, 4, 5, 4000, 5285, 5290, 5300, 5320, 8990, d):
+        ctx = bts.BtsContext(1, d, K, K)
+        t = torch.from_numpy(x.copy()).to(D)
+        oi = torch.zeros(K, dtype=torch.int32, device=D)
+        ov = torch.zeros(K, dtype=torch.float32, device=D)
+        bts.downlink_topk(ctx, t, oi, ov)
+        torch.cuda.synchronize()
+        h = x.copy()
+        wi, wv = oracle.downlink(h, K)
+        G.assert_same_bits(oi, wi, f"K={K} idx")
+        G.assert_same_bits(ov, wv, f"K={K} val")
+        G.assert_same_bits(t, h, f"K={K} residual")
+
+
+def test_denormals_survive_error_compensation(G, oracle):
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(3)
+    N, d, K = 2, 4100, 40
+    g = (rng.standard_normal((N, d)) * 1e-38).astype(np.float32)      # products are denormal
+    e = (rng.standard_normal((N, d)) * 1e-40).astype(np.float32)
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    tg, te = torch.from_numpy(g).to(D), torch.from_numpy(e).to(D)
+    ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+    bts.topk_compress(ctx, tg, te, 0.01, ui, uv)
+    torch.cuda.synchronize()
+    h = e.copy()
+    wi, wv = oracle.worker_stage(g, h, 0.01, K)
+    assert np.count_nonzero(h) > d, "the expected residuals must contain denormals"
+    G.assert_same_bits(ui, wi, "up_idx")
+    G.assert_same_bits(uv, wv, "up_val")
+    G.assert_same_bits(te, h, "eps")
+
+
+@pytest.mark.parametrize("N,d,K", [(1, 100, 10), (4, 5000, 50), (16, 200_003, 2001),
+                                   (64, 50_001, 500), (300, 4096, 64)])
+def test_sparse_aggregate(G, oracle, N, d, K):
+    """Fixed worker order, one fused multiply-add per term, non-dyadic weights, heavy
+    collisions between workers; untouched coordinates (including -0) keep their bits."""
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(N + d + K)
+    # concentrate the indices so that many workers hit the same coordinates
+    hot = max(K, d // 8)
+    up_idx = np.stack([np.sort(rng.choice(hot, size=K, replace=False)) for _ in range(N)]
+                      ).astype(np.uint32)
+    up_idx[N // 2:] += np.uint32(d - hot)          # second half of the workers at the far end
+    up_val = rng.standard_normal((N, K)).astype(np.float32)
+    p = rng.dirichlet(np.ones(N)).astype(np.float32)
+    delta = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    delta[::7] = -0.0
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    ti = torch.from_numpy(up_idx.view(np.int32)).to(D)
+    tv, tp, td = (torch.from_numpy(a).to(D) for a in (up_val, p, delta))
+    nnz = torch.zeros(1, dtype=torch.int32, device=D)
+    bts.sparse_aggregate(ctx, ti, tv, tp, td, nnz)
+    torch.cuda.synchronize()
+    h = delta.copy()
+    want_nnz = oracle.aggregate(up_idx, up_val, p, h)
+    G.assert_same_bits(td, h, "g_t")
+    assert int(nnz.item()) == want_nnz
+    # union_nnz is optional
+    td2 = torch.from_numpy(delta).to(D)
+    bts.sparse_aggregate(ctx, ti, tv, tp, td2, None)
+    torch.cuda.synchronize()
+    G.assert_same_bits(td2, h, "g_t without union_nnz")
+
+
+def test_sparse_sgd_update(G, oracle):
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(4)
+    d, K = 100_000, 777
+    idx = np.sort(rng.choice(d, K, replace=False)).astype(np.uint32)
+    val = rng.standard_normal(K).astype(np.float32)
+    w = rng.standard_normal(d).astype(np.float32)
+    D = G.dev()
+    ctx = bts.BtsContext(1, d, K, K)
+    tw = torch.from_numpy(w).to(D)
+    bts.sparse_sgd_update(ctx, torch.from_numpy(idx.view(np.int32)).to(D),
+                          torch.from_numpy(val).to(D), K, 0.013, tw)
+    torch.cuda.synchronize()
+    h = w.copy()
+    oracle.update(idx, val, 0.013, h)
+    G.assert_same_bits(tw, h, "w")
+
+
+SMALL = {"C1": 60_001, "C2": 120_002, "C3": 90_008, "C4": 70_003, "C5": 150_000}
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("mode", ["paper", "literal"])
+def test_bidir_step_scaled_configs(G, oracle, name, mode):
+    """Each benchmark recipe at a d the oracle finishes in seconds (several chunks and a
+    ragged tail), a few steps with carried residuals, in the paper's form
+    (alpha inside a^q, update without alpha) and in the form with the step size applied at
+    the update."""
+    cfg = wl.CONFIGS[name].scaled(SMALL[name], steps=3)
+    if cfg.N > 16:
+        cfg = wl.CONFIGS[name].scaled(SMALL[name], N=16, steps=3)
+    a_in, a_out = (cfg.alpha, 1.0) if mode == "paper" else (1.0, cfg.alpha)
+    src = wl.GradientSource(cfg, G.dev())
+    p = wl.p_weights(cfg) if cfg.N == wl.CONFIGS[name].N else \
+        wl.p_weights(wl.CONFIGS[name])[:cfg.N].copy()
+    st = G.GpuState(cfg.N, cfg.d, cfg.K_up, cfg.K_dn, wl.weights0(cfg, "cpu").numpy(), p)
+    for t in range(1, cfg.steps + 1):
+        st.step_and_compare(oracle, src.step(t), a_in, a_out, f"{cfg.name} step {t}")
+
+
+def test_bidir_step_equals_the_four_calls_and_is_deterministic(G):
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS["C4"].scaled(80_005, N=8, steps=2)
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p = torch.from_numpy(wl.p_weights(wl.CONFIGS["C4"])[:8].copy()).to(D)
+    runs = []
+    for variant in ("step", "calls", "step"):
+        ctx = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn)
+        eps = torch.zeros((cfg.N, cfg.d), device=D)
+        delta = torch.zeros(cfg.d, device=D)
+        w = wl.weights0(cfg, D)
+        ui = torch.zeros((cfg.N, cfg.K_up), dtype=torch.int32, device=D)
+        uv = torch.zeros((cfg.N, cfg.K_up), device=D)
+        di = torch.zeros(cfg.K_dn, dtype=torch.int32, device=D)
+        dv = torch.zeros(cfg.K_dn, device=D)
+        for t in (1, 2):
+            g = src.step(t)
+            if variant == "step":
+                bts.bidir_step(ctx, g, eps, delta, w, p, cfg.alpha, 1.0, ui, uv, di, dv, None)
+            else:
+                bts.topk_compress(ctx, g, eps, cfg.alpha, ui, uv)
+                bts.sparse_aggregate(ctx, ui, uv, p, delta, None)
+                bts.downlink_topk(ctx, delta, di, dv)
+                bts.sparse_sgd_update(ctx, di, dv, cfg.K_dn, 1.0, w)
+        torch.cuda.synchronize()
+        runs.append([t.clone() for t in (eps, delta, w, ui, uv, di, dv)])
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_misaligned_buffers_are_rejected(G):
+    import paper_2209_15203_amd as bts
+    D = G.dev()
+    ctx = bts.BtsContext(1, 64, 4, 4)
+    buf = torch.zeros(65 + 4, device=D)
+    off = buf[1:65]                      # 4-byte aligned only
+    ui = torch.zeros(4, dtype=torch.int32, device=D)
+    uv = torch.zeros(4, device=D)
+    with pytest.raises(bts.BtsError):
+        bts.downlink_topk(ctx, off, ui, uv)
+    with pytest.raises(bts.BtsError):
+        bts.topk_compress(ctx, off, torch.zeros(64, device=D), 1.0, ui, uv)
