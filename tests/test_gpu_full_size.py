@@ -1,0 +1,122 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+For the first steps of every configuration the oracle computes the whole step and every
+output is compared bit for bit.  For the remaining steps (the oracle would need minutes)
+a few sampled worker rows are still compared bit for bit -- worker rows are independent,
+so the oracle can follow them alone -- and the rest is checked through properties that
+hold at any size: the Top_K invariants on every row (K strictly ascending indices,
+residual +0 at the kept positions, min |sent| >= max |residual|), the model moving by
+exactly the downlink message, and the conservation identity of Lemma 1 in fp64.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+# config -> number of steps the oracle computes in full
+FULL_STEPS = {"C1": 3, "C2": 3, "C3": 2, "C4": 2, "C5": 1}
+MAG = 0x7FFFFFFF
+
+
+def mag(t: torch.Tensor) -> torch.Tensor:
+    return t.view(torch.int32) & MAG
+
+
+def corrected_sequence(w, eps, delta, p):
+    """w~ = w - sum_q p_q eps^q - delta (the error-corrected sequence of Lemma 1), fp64."""
+    acc = w.double() - delta.double()
+    for q in range(eps.shape[0]):
+        acc -= float(p[q]) * eps[q].double()
+    return acc
+
+
+def check_message_invariants(idx, val, residual, K, d, what):
+    i64 = idx.long()
+    assert idx.shape[-1] == K
+    assert bool((i64[..., 1:] > i64[..., :-1]).all()), f"{what}: indices not strictly ascending"
+    assert int(i64.min()) >= 0 and int(i64.max()) < d
+    kept = torch.gather(residual, -1, i64)
+    assert not bool(kept.view(torch.int32).any()), f"{what}: residual not +0 at kept positions"
+    lo_sent = mag(val).amin(dim=-1)
+    hi_res = mag(residual).amax(dim=-1)
+    assert bool((lo_sent >= hi_res).all()), f"{what}: a residual exceeds a sent magnitude"
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_full_size_config(oracle, name):
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS[name]
+    N, d = cfg.N, cfg.d
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p_host = wl.p_weights(cfg)
+    w0 = wl.weights0(cfg, D)
+    ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn)
+    eps = torch.zeros((N, d), dtype=torch.float32, device=D)
+    delta = torch.zeros(d, dtype=torch.float32, device=D)
+    w = w0.clone()
+    p = torch.from_numpy(p_host).to(D)
+    ui = torch.zeros((N, cfg.K_up), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, cfg.K_up), dtype=torch.float32, device=D)
+    di = torch.zeros(cfg.K_dn, dtype=torch.int32, device=D)
+    dv = torch.zeros(cfg.K_dn, dtype=torch.float32, device=D)
+    nnz = torch.zeros(1, dtype=torch.int32, device=D)
+    g = torch.empty((N, d), dtype=torch.float32, device=D)
+
+    n_full = min(FULL_STEPS[name], cfg.steps)
+    sampled = sorted({0, N // 3, N - 1})
+    h_eps = np.zeros((N, d), np.float32)
+    h_delta = np.zeros(d, np.float32)
+    h_w = w0.cpu().numpy().copy()
+    h_rows = None
+
+    for t in range(1, cfg.steps + 1):
+        src.fill(t, g)
+        full = t <= n_full
+        if not full:
+            wt_before = corrected_sequence(w, eps, delta, p_host)
+            w_before = w.clone()
+        print(f"[{name}] step {t}/{cfg.steps} ({'full oracle' if full else 'sampled rows'})",
+              flush=True)
+        bts.bidir_step(ctx, g, eps, delta, w, p, cfg.alpha, 1.0, ui, uv, di, dv, nnz)
+        torch.cuda.synchronize()
+        tag = f"{name} step {t}"
+        if full:
+            want = oracle.bidir_step(g.cpu().numpy(), h_eps, h_delta, h_w, p_host, cfg.K_up,
+                                     cfg.K_dn, cfg.alpha, 1.0)
+            G.assert_same_bits(ui, want["up_idx"], f"{tag} up_idx")
+            G.assert_same_bits(uv, want["up_val"], f"{tag} up_val")
+            G.assert_same_bits(eps, h_eps, f"{tag} eps")
+            G.assert_same_bits(di, want["dn_idx"], f"{tag} dn_idx")
+            G.assert_same_bits(dv, want["dn_val"], f"{tag} dn_val")
+            G.assert_same_bits(delta, h_delta, f"{tag} delta")
+            G.assert_same_bits(w, h_w, f"{tag} w")
+            assert int(nnz.item()) == want["union_nnz"]
+            if t == n_full and cfg.steps > n_full:
+                h_rows = np.ascontiguousarray(h_eps[sampled])
+                del h_eps
+        else:
+            # sampled worker rows: bit-exact against the oracle
+            g_rows = g[sampled].cpu().numpy()
+            want_i, want_v = oracle.worker_stage(g_rows, h_rows, cfg.alpha, cfg.K_up)
+            G.assert_same_bits(ui[sampled], want_i, f"{tag} up_idx rows {sampled}")
+            G.assert_same_bits(uv[sampled], want_v, f"{tag} up_val rows {sampled}")
+            G.assert_same_bits(eps[sampled], h_rows, f"{tag} eps rows {sampled}")
+            # every row and the server stage: properties
+            check_message_invariants(ui, uv, eps, cfg.K_up, d, f"{tag} uplink")
+            check_message_invariants(di, dv, delta, cfg.K_dn, d, f"{tag} downlink")
+            assert 0 < int(nnz.item()) <= N * cfg.K_up
+            moved = w_before.clone()
+            moved[di.long()] = w_before[di.long()] - dv          # exact: one rounding, as fma
+            assert torch.equal(moved.view(torch.int32), w.view(torch.int32)), f"{tag} w"
+            step_dir = torch.zeros(d, dtype=torch.float64, device=D)
+            for q in range(N):
+                step_dir += float(p_host[q]) * g[q].double()
+            wt_after = corrected_sequence(w, eps, delta, p_host)
+            err = (wt_after - (wt_before - float(np.float32(cfg.alpha)) * step_dir)).abs().max()
+            assert float(err) < 2e-6, f"{tag}: Lemma 1 identity off by {float(err)}"

@@ -63,3 +63,16 @@ def test_distributions_have_the_stated_scale():
     assert lg.max() > -2.5 and np.median(lg) < -2.0      # several decades of scale
     w = wl.weights0(cfg5, "cpu")
     assert abs(w.std().item() - 0.1) < 0.005
+
+
+def test_transforms_are_finite_at_the_extreme_counters():
+    ext = torch.tensor([0, -1, 1 << 62, -(1 << 63), (1 << 63) - 1, 1 << 40, (1 << 40) - 1],
+                       dtype=torch.int64)
+    for f in (wl.normal_from_bits, wl.laplace_from_bits, wl.student_t2_from_bits):
+        v = f(ext)
+        assert bool(torch.isfinite(v).all()), f.__name__
+    # and over a large sweep of the top bits
+    hi = (torch.arange(0, 1 << 24, 7, dtype=torch.int64) << 40)
+    for f in (wl.normal_from_bits, wl.laplace_from_bits, wl.student_t2_from_bits):
+        assert bool(torch.isfinite(f(hi)).all()), f.__name__
+        assert bool(torch.isfinite(f(hi | ((1 << 40) - 1))).all()), f.__name__

@@ -82,13 +82,15 @@ def normal_from_bits(z: torch.Tensor) -> torch.Tensor:
 
 def laplace_from_bits(z: torch.Tensor) -> torch.Tensor:
     """Laplace(0, 1) by inverse CDF."""
-    u = (_u24_hi(z).to(torch.float32) + 0.5) * (1.0 / (1 << 24)) - 0.5  # (-0.5, 0.5)
+    # centred integer first, so that every step is exact in fp32 and |u| < 0.5 strictly
+    u = ((_u24_hi(z) - (1 << 23)).to(torch.float32) + 0.5) * (1.0 / (1 << 24))
     return -torch.sign(u) * torch.log1p(-2.0 * torch.abs(u))
 
 
 def student_t2_from_bits(z: torch.Tensor) -> torch.Tensor:
     """Student-t with 2 degrees of freedom by its closed-form inverse CDF."""
-    u = (_u24_hi(z).to(torch.float32) + 0.5) * (1.0 / (1 << 24))       # (0, 1)
+    # 23 bits: (k + 0.5) / 2^23 is exact in fp32 and stays strictly inside (0, 1)
+    u = (_lsr(z, 41).to(torch.float32) + 0.5) * (1.0 / (1 << 23))
     return (2.0 * u - 1.0) / torch.sqrt(2.0 * u * (1.0 - u))
 
 
