@@ -129,6 +129,12 @@ int bts_profile_read(bts_ctx* ctx, double* ms_total, uint64_t* launches);
  * which: 0 = uplink, 1 = downlink. */
 int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_dense);
 
+/* Testing aid: which select path later calls on this context take.  0 (default): chosen
+ * by shape; 1: the dense multi-pass path only (the path that also serves as the
+ * fallback); 2: the single-pass path wherever the shape allows it (d >= 65536 and
+ * K <= d/64), whatever its size.  Results are identical in every mode. */
+int bts_set_path(bts_ctx* ctx, int mode);
+
 #ifdef __cplusplus
 }
 #endif

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libbts.so")
 
 EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
            "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
-           "bts_profile_enable", "bts_profile_read", "bts_last_path"]
+           "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path"]
 
 _lib = None
 
@@ -48,6 +48,7 @@ def load_library():
     lib.bts_profile_enable.argtypes = [vp, C.c_int]
     lib.bts_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64)]
     lib.bts_last_path.argtypes = [vp, C.c_int, C.POINTER(u32), C.POINTER(u32)]
+    lib.bts_set_path.argtypes = [vp, C.c_int]
     for name in EXPORTS:
         if name != "bts_destroy":
             getattr(lib, name).restype = C.c_int
@@ -110,6 +111,10 @@ class BtsContext:
         ms, n = C.c_double(0.0), C.c_uint64(0)
         self.check(self._lib.bts_profile_read(self._h, C.byref(ms), C.byref(n)), "bts_profile_read")
         return ms.value, n.value
+
+    def set_path(self, mode: int) -> None:
+        """0 = by shape, 1 = dense path only, 2 = single-pass path wherever possible."""
+        self.check(self._lib.bts_set_path(self._h, int(mode)), "bts_set_path")
 
     def last_path(self, which: int) -> Tuple[int, int]:
         a, b = C.c_uint32(0), C.c_uint32(0)

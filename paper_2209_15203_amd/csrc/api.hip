@@ -18,8 +18,12 @@ struct bts_ctx {
   int device;
   int last_hip_error;
   DenseScratch dense;
+  FastPlan plan_up, plan_dn;
+  FastScratch fast_up, fast_dn;
+  std::vector<void*> owned;     // every device allocation of the context
   // timing of the dominant kernel
   bool profile;
+  int path_mode;                // 0 = by shape, 1 = dense only, 2 = single-pass where possible
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;
   size_t ev_used;
 };
@@ -33,16 +37,36 @@ int fail_hip(bts_ctx* ctx, hipError_t e) {
   return BTS_EHIP;
 }
 
+// Zero-filled device allocation owned by the context.
 template <typename T>
-hipError_t dev_alloc(T** p, size_t count) {
-  return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T) + 16);
+bool dev_alloc(bts_ctx* ctx, T** p, size_t count) {
+  void* q = nullptr;
+  const size_t bytes = count * sizeof(T) + 16;
+  if (hipMalloc(&q, bytes) != hipSuccess) return false;
+  ctx->owned.push_back(q);
+  if (hipMemset(q, 0, bytes) != hipSuccess) return false;
+  *p = reinterpret_cast<T*>(q);
+  return true;
+}
+
+bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc) {
+  if (!pl.enabled) return true;
+  uint8_t* sel = nullptr;
+  bool ok = dev_alloc(ctx, &sc->sample_hist, (size_t)rows * 8192) &&
+            dev_alloc(ctx, &sc->lower_key, rows) && dev_alloc(ctx, &sc->cand_cnt, rows) &&
+            dev_alloc(ctx, &sc->cand, (size_t)rows * pl.cap) &&
+            dev_alloc(ctx, &sc->hist, (size_t)rows * 2048) && dev_alloc(ctx, &sc->done, rows) &&
+            dev_alloc(ctx, &sel, (size_t)rows * fast_sel_bytes()) &&
+            dev_alloc(ctx, &sc->need, rows) &&
+            dev_alloc(ctx, &sc->bitmap, (size_t)rows * pl.words_per_row) &&
+            dev_alloc(ctx, &sc->bucket_cnt, (size_t)rows * pl.nbk) &&
+            dev_alloc(ctx, &sc->bucket_off, (size_t)rows * pl.nbk);
+  sc->sel = sel;
+  return ok;
 }
 
 void release(bts_ctx* ctx) {
-  (void)hipFree(ctx->dense.hist);
-  (void)hipFree(ctx->dense.state);
-  (void)hipFree(ctx->dense.cnt_gt);
-  (void)hipFree(ctx->dense.cnt_eq);
+  for (void* q : ctx->owned) (void)hipFree(q);
   for (auto& pr : ctx->ev_pool) {
     (void)hipEventDestroy(pr.first);
     (void)hipEventDestroy(pr.second);
@@ -68,14 +92,31 @@ void profile_events(bts_ctx* ctx, hipEvent_t* e0, hipEvent_t* e1) {
   ctx->ev_used++;
 }
 
-int run_select(bts_ctx* ctx, const float* g, float* x, uint32_t rows, uint32_t K, float alpha,
-               uint32_t* idx, float* val, bool dominant) {
+bool use_fast(const bts_ctx* ctx, const FastPlan& pl) {
+  if (!pl.enabled || ctx->path_mode == 1) return false;
+  return ctx->path_mode == 2 || pl.preferred;
+}
+
+// uplink = true: the N worker rows with the error compensation fused in; false: the one
+// server row.  The single-pass path runs first where the plan enables it; rows it flags
+// (and every row where it is not enabled) go through the dense path.
+int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha, uint32_t* idx,
+               float* val) {
+  const uint32_t rows = uplink ? (uint32_t)ctx->N : 1u;
+  const uint32_t K = uplink ? ctx->K_up : ctx->K_dn;
+  const FastPlan& pl = uplink ? ctx->plan_up : ctx->plan_dn;
+  const FastScratch& fs = uplink ? ctx->fast_up : ctx->fast_dn;
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (dominant) profile_events(ctx, &e0, &e1);
+  if (uplink) profile_events(ctx, &e0, &e1);
   hipError_t e;
   if (K == 0) {
     if (g == nullptr) return BTS_OK;
     e = axpy_only(ctx->stream, g, x, rows, ctx->d, alpha, e0, e1);
+  } else if (use_fast(ctx, pl)) {
+    e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
+    if (e == hipSuccess)
+      e = dense_select(ctx->stream, ctx->dense, nullptr, x, rows, ctx->d, K, 0.0f, idx, val,
+                       fs.need, true, nullptr, nullptr);
   } else {
     e = dense_select(ctx->stream, ctx->dense, g, x, rows, ctx->d, K, alpha, idx, val, nullptr,
                      false, e0, e1);
@@ -103,7 +144,10 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->last_hip_error = 0;
   ctx->profile = false;
   ctx->ev_used = 0;
+  ctx->path_mode = 0;
   ctx->dense = DenseScratch{};
+  ctx->fast_up = FastScratch{};
+  ctx->fast_dn = FastScratch{};
   if (hipGetDevice(&ctx->device) != hipSuccess) {
     delete ctx;
     return BTS_EHIP;
@@ -111,10 +155,14 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   const uint32_t rows = (uint32_t)N;
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
   ctx->dense.nwc = nwc;
-  bool ok = dev_alloc(&ctx->dense.hist, (size_t)rows * kBins0) == hipSuccess &&
-            dev_alloc(&ctx->dense.state, (size_t)rows) == hipSuccess &&
-            dev_alloc(&ctx->dense.cnt_gt, (size_t)rows * nwc) == hipSuccess &&
-            dev_alloc(&ctx->dense.cnt_eq, (size_t)rows * nwc) == hipSuccess;
+  ctx->plan_up = fast_plan(rows, d, K_up);
+  ctx->plan_dn = fast_plan(1, d, K_dn);
+  bool ok = dev_alloc(ctx, &ctx->dense.hist, (size_t)rows * kBins0) &&
+            dev_alloc(ctx, &ctx->dense.state, (size_t)rows) &&
+            dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
+            dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
+            alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up) &&
+            alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn);
   if (!ok) {
     (void)hipGetLastError();
     release(ctx);
@@ -136,7 +184,7 @@ int topk_compress(bts_ctx* ctx, const float* g, float* eps, float alpha_in, uint
                   float* up_val) {
   if (!ctx || !g || !eps || !aligned16(g) || !aligned16(eps)) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
-  return run_select(ctx, g, eps, (uint32_t)ctx->N, ctx->K_up, alpha_in, up_idx, up_val, true);
+  return run_select(ctx, true, g, eps, alpha_in, up_idx, up_val);
 }
 
 int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, const float* p,
@@ -151,7 +199,7 @@ int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, 
 int downlink_topk(bts_ctx* ctx, float* delta, uint32_t* dn_idx, float* dn_val) {
   if (!ctx || !delta || !aligned16(delta)) return BTS_EINVAL;
   if (ctx->K_dn > 0 && (!dn_idx || !dn_val)) return BTS_EINVAL;
-  return run_select(ctx, nullptr, delta, 1, ctx->K_dn, 0.0f, dn_idx, dn_val, false);
+  return run_select(ctx, false, nullptr, delta, 0.0f, dn_idx, dn_val);
 }
 
 int sparse_sgd_update(bts_ctx* ctx, const uint32_t* idx, const float* val, uint32_t K,
@@ -204,8 +252,28 @@ int bts_profile_read(bts_ctx* ctx, double* ms_total, uint64_t* launches) {
 
 int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_dense) {
   if (!ctx || !rows_fast || !rows_dense || (which != 0 && which != 1)) return BTS_EINVAL;
+  const uint32_t rows = which == 0 ? (uint32_t)ctx->N : 1u;
+  const FastPlan& pl = which == 0 ? ctx->plan_up : ctx->plan_dn;
+  const FastScratch& fs = which == 0 ? ctx->fast_up : ctx->fast_dn;
+  const uint32_t K = which == 0 ? ctx->K_up : ctx->K_dn;
   *rows_fast = 0;
-  *rows_dense = which == 0 ? (uint32_t)ctx->N : 1u;
+  *rows_dense = rows;
+  if (!use_fast(ctx, pl) || K == 0) return BTS_OK;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  std::vector<uint32_t> need(rows);
+  e = hipMemcpy(need.data(), fs.need, rows * sizeof(uint32_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  uint32_t dense = 0;
+  for (uint32_t v : need) dense += v ? 1u : 0u;
+  *rows_dense = dense;
+  *rows_fast = rows - dense;
+  return BTS_OK;
+}
+
+int bts_set_path(bts_ctx* ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 2) return BTS_EINVAL;
+  ctx->path_mode = mode;
   return BTS_OK;
 }
 

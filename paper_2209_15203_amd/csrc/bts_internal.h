@@ -48,6 +48,39 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
                      float alpha, hipEvent_t ev0, hipEvent_t ev1);
 
+// ---- speculative single-pass select (exact; flags rows it cannot finish) -----------------
+struct FastPlan {
+  bool enabled;            // false: shape is served by the dense path alone (no scratch)
+  bool preferred;          // the default choice for this shape
+  uint32_t stride;         // every stride-th 256-coordinate slice is sampled
+  uint32_t target;         // sampled coordinates wanted at or above the lower bound
+  uint32_t cap;            // candidate list capacity per row
+  uint32_t nbk;            // 4096-coordinate buckets per row
+  uint64_t words_per_row;  // bitmap words per row
+};
+
+struct FastScratch {
+  uint32_t* sample_hist;   // rows x 8192 (zero between calls)
+  uint32_t* lower_key;     // rows
+  uint32_t* cand_cnt;      // rows
+  uint2* cand;             // rows x cap (index, value bits)
+  uint32_t* hist;          // rows x 2048 (zero between calls)
+  uint32_t* done;          // rows (zero between calls)
+  void* sel;               // rows x fast_sel_bytes()
+  uint32_t* need;          // rows: 1 = the dense path must redo this row
+  uint32_t* bitmap;        // rows x words_per_row (zero between calls)
+  uint32_t* bucket_cnt;    // rows x nbk (zero between calls)
+  uint32_t* bucket_off;    // rows x nbk
+};
+
+FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K);
+size_t fast_sel_bytes();
+// Same contract as dense_select, except that rows whose need flag is set on return are
+// left unselected (x already holds fma(alpha, g, x) for every row).
+hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
+                       float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
+                       uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1);
+
 // ---- server side ------------------------------------------------------------------------
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz);

@@ -24,23 +24,42 @@ def tied_rows(rng, N, d, levels=3):
 
 SHAPES = [
     # N, d, K   (ragged rows: d % 4 != 0 puts rows off 16-byte alignment; d below one chunk;
-    #            several chunks and a tail; K = 1, K = d)
+    #            several chunks and a tail; K = 1, K = d; from d = 65536 on and K <= d/64 the
+    #            single-pass path is possible and path mode 2 takes it)
     (1, 1, 1), (3, 5, 2), (2, 63, 7), (4, 1000, 10), (3, 2049, 33), (5, 4099, 4099),
     (2, 10007, 1), (7, 30011, 301), (4, 65536, 66), (3, 100003, 1001), (2, 262147, 5000),
+    (1, 70001, 1), (5, 65537, 1024), (2, 262147, 3000), (3, 1048579, 1049), (9, 300001, 37),
 ]
+DENSE, SINGLE_PASS = 1, 2
+
+
+def make_rows(rng, kind, N, d):
+    """(g, eps0, alpha) for one compress call."""
+    if kind == "normal":
+        return (rng.standard_normal((N, d)).astype(np.float32),
+                (rng.standard_normal((N, d)) * 0.5).astype(np.float32), 0.37)
+    if kind == "ties":                      # three magnitudes: the candidate list overflows
+        return tied_rows(rng, N, d), np.zeros((N, d), np.float32), 1.0
+    if kind == "quantized":                 # a grid of values: small tie groups at the threshold
+        g = (np.round(rng.standard_normal((N, d)) * 256) / 256).astype(np.float32)
+        return g, np.zeros((N, d), np.float32), 1.0
+    if kind == "mixed":                     # some rows finish in one pass, some fall back
+        g = rng.standard_normal((N, d)).astype(np.float32)
+        g[::2] = tied_rows(rng, len(g[::2]), d)
+        return g, np.zeros((N, d), np.float32), 1.0
+    raise ValueError(kind)
 
 
 @pytest.mark.parametrize("N,d,K", SHAPES)
-@pytest.mark.parametrize("kind", ["normal", "ties"])
-def test_topk_compress(G, oracle, N, d, K, kind):
+@pytest.mark.parametrize("kind", ["normal", "ties", "quantized", "mixed"])
+@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS])
+def test_topk_compress(G, oracle, N, d, K, kind, path):
     import paper_2209_15203_amd as bts
     rng = np.random.default_rng(N * 1000003 + d * 7 + K)
-    g = rng.standard_normal((N, d)).astype(np.float32) if kind == "normal" else tied_rows(rng, N, d)
-    eps0 = (rng.standard_normal((N, d)) * 0.5).astype(np.float32) if kind == "normal" \
-        else np.zeros((N, d), np.float32)
-    alpha = 0.37 if kind == "normal" else 1.0
+    g, eps0, alpha = make_rows(rng, kind, N, d)
     D = G.dev()
     ctx = bts.BtsContext(N, d, K, K)
+    ctx.set_path(path)
     tg, te = torch.from_numpy(g).to(D), torch.from_numpy(eps0).to(D)
     ui = torch.full((N, K), -1, dtype=torch.int32, device=D)
     uv = torch.zeros((N, K), dtype=torch.float32, device=D)
@@ -52,6 +71,17 @@ def test_topk_compress(G, oracle, N, d, K, kind):
     G.assert_same_bits(uv, want_v, "up_val")
     G.assert_same_bits(te, h_eps, "eps")
     G.assert_same_bits(tg, g, "g must not be modified")
+    fast, dense = ctx.last_path(0)
+    assert fast + dense == N
+    if path == SINGLE_PASS and d >= 65536 and K * 64 <= d:
+        if kind in ("normal", "quantized"):
+            assert fast == N, "iid rows must finish in the single pass"
+        if kind == "ties":
+            assert dense == N, "three-valued rows overflow the candidate list"
+        if kind == "mixed" and N > 1:
+            assert 0 < fast < N
+    else:
+        assert fast == 0
 
 
 def test_k_zero_is_plain_error_accumulation(G, oracle):
@@ -79,8 +109,10 @@ def test_threshold_run_spanning_many_workgroups(G, oracle):
     x[0::3], x[1::3], x[2::3] = 1.0, -2.0, 3.0
     n3, n2 = len(x[2::3]), len(x[1::3])
     D = G.dev()
-    for K in (n3 + n2 + 123_457, n3 - 5, n3 + 1, 17):
+    for K, path in ((n3 + n2 + 123_457, DENSE), (n3 - 5, DENSE), (n3 + 1, 0), (17, DENSE),
+                    (17, SINGLE_PASS), (40_000, SINGLE_PASS)):
         ctx = bts.BtsContext(1, d, K, K)
+        ctx.set_path(path)
         t = torch.from_numpy(x.copy()).to(D)
         oi = torch.zeros(K, dtype=torch.int32, device=D)
         ov = torch.zeros(K, dtype=torch.float32, device=D)
@@ -93,11 +125,11 @@ def test_threshold_run_spanning_many_workgroups(G, oracle):
         G.assert_same_bits(t, h, f"K={K} residual")
 
 
-def test_special_values_are_ordered_by_magnitude_bits(G, oracle):
+@pytest.mark.parametrize("d,path", [(9001, DENSE), (200_001, DENSE), (200_001, SINGLE_PASS)])
+def test_special_values_are_ordered_by_magnitude_bits(G, oracle, d, path):
     """NaN > Inf > finite > denormal > zero, +0 ties with -0, values copied bit for bit."""
     import paper_2209_15203_amd as bts
     rng = np.random.default_rng(2)
-    d = 9001
     x = rng.standard_normal(d).astype(np.float32)
     xb = x.view(np.uint32)
     xb[10] = 0x7FC00001          # NaN with payload
@@ -110,8 +142,11 @@ def test_special_values_are_ordered_by_magnitude_bits(G, oracle):
     xb[200:300] = 0x00000000     # +0
     x[300:4000] = 0.0
     D = G.dev()
-    for K in (1, 2, 3, 4, 5, 4000, 5285, 5290, 5300, 5320, 8990, d):
+    ks = (1, 2, 3, 4, 5, 4000, 5285, 5290, 5300, 5320, 8990, d) if d < 10_000 else \
+        (1, 2, 3, 4, 5, 100, 3000)
+    for K in ks:
         ctx = bts.BtsContext(1, d, K, K)
+        ctx.set_path(path)
         t = torch.from_numpy(x.copy()).to(D)
         oi = torch.zeros(K, dtype=torch.int32, device=D)
         ov = torch.zeros(K, dtype=torch.float32, device=D)
@@ -197,12 +232,13 @@ def test_sparse_sgd_update(G, oracle):
     G.assert_same_bits(tw, h, "w")
 
 
-SMALL = {"C1": 60_001, "C2": 120_002, "C3": 90_008, "C4": 70_003, "C5": 150_000}
+SMALL = {"C1": 70_001, "C2": 120_002, "C3": 90_008, "C4": 70_003, "C5": 150_000}
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 @pytest.mark.parametrize("mode", ["paper", "literal"])
-def test_bidir_step_scaled_configs(G, oracle, name, mode):
+@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS])
+def test_bidir_step_scaled_configs(G, oracle, name, mode, path):
     """Each benchmark recipe at a d the oracle finishes in seconds (several chunks and a
     ragged tail), a few steps with carried residuals, in the paper's form
     (alpha inside a^q, update without alpha) and in the form with the step size applied at
@@ -215,8 +251,11 @@ def test_bidir_step_scaled_configs(G, oracle, name, mode):
     p = wl.p_weights(cfg) if cfg.N == wl.CONFIGS[name].N else \
         wl.p_weights(wl.CONFIGS[name])[:cfg.N].copy()
     st = G.GpuState(cfg.N, cfg.d, cfg.K_up, cfg.K_dn, wl.weights0(cfg, "cpu").numpy(), p)
+    st.ctx.set_path(path)
     for t in range(1, cfg.steps + 1):
         st.step_and_compare(oracle, src.step(t), a_in, a_out, f"{cfg.name} step {t}")
+        if path == SINGLE_PASS:
+            assert st.ctx.last_path(0)[0] > 0, "no uplink row took the single-pass path"
 
 
 def test_bidir_step_equals_the_four_calls_and_is_deterministic(G):
@@ -226,8 +265,9 @@ def test_bidir_step_equals_the_four_calls_and_is_deterministic(G):
     src = wl.GradientSource(cfg, D)
     p = torch.from_numpy(wl.p_weights(wl.CONFIGS["C4"])[:8].copy()).to(D)
     runs = []
-    for variant in ("step", "calls", "step"):
+    for variant in ("step", "calls", "step", "dense"):
         ctx = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn)
+        ctx.set_path(DENSE if variant == "dense" else SINGLE_PASS)
         eps = torch.zeros((cfg.N, cfg.d), device=D)
         delta = torch.zeros(cfg.d, device=D)
         w = wl.weights0(cfg, D)
@@ -237,7 +277,7 @@ def test_bidir_step_equals_the_four_calls_and_is_deterministic(G):
         dv = torch.zeros(cfg.K_dn, device=D)
         for t in (1, 2):
             g = src.step(t)
-            if variant == "step":
+            if variant in ("step", "dense"):
                 bts.bidir_step(ctx, g, eps, delta, w, p, cfg.alpha, 1.0, ui, uv, di, dv, None)
             else:
                 bts.topk_compress(ctx, g, eps, cfg.alpha, ui, uv)
