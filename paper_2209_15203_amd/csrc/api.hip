@@ -53,9 +53,10 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
   if (!pl.enabled) return true;
   uint8_t* sel = nullptr;
   bool ok = dev_alloc(ctx, &sc->sample_hist, (size_t)rows * 8192) &&
-            dev_alloc(ctx, &sc->lower_key, rows) && dev_alloc(ctx, &sc->cand_cnt, rows) &&
-            dev_alloc(ctx, &sc->cand, (size_t)rows * pl.cap) &&
-            dev_alloc(ctx, &sc->hist, (size_t)rows * 2048) && dev_alloc(ctx, &sc->done, rows) &&
+            dev_alloc(ctx, &sc->lower_key, rows) &&
+            dev_alloc(ctx, &sc->cand_cnt, (size_t)rows * fast_sublists() * fast_counter_stride()) &&
+            dev_alloc(ctx, &sc->cand, (size_t)rows * fast_sublists() * pl.cap) &&
+            dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_blocks() * 2048) &&
             dev_alloc(ctx, &sel, (size_t)rows * fast_sel_bytes()) &&
             dev_alloc(ctx, &sc->need, rows) &&
             dev_alloc(ctx, &sc->bitmap, (size_t)rows * pl.words_per_row) &&

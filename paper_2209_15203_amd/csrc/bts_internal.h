@@ -9,9 +9,9 @@ namespace bts {
 constexpr int kWave = 64;                 // CDNA wavefront
 constexpr int kBlock = 256;               // threads per workgroup in the dense passes
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kUnroll = 8;                // float4 loads in flight per lane and array
+constexpr int kUnroll = 4;                // float4 loads in flight per lane and array
 // A wave owns kWaveChunk consecutive coordinates (absolute, 16-byte aligned offsets).
-constexpr uint32_t kWaveChunk = kWave * 4 * kUnroll;   // 2048
+constexpr uint32_t kWaveChunk = kWave * 4 * kUnroll;   // 1024
 constexpr int kBins0 = 2048;              // first digit: key bits 30..20
 constexpr int kBinsLo = 1024;             // second and third digit: bits 19..10, 9..0
 
@@ -54,7 +54,7 @@ struct FastPlan {
   bool preferred;          // the default choice for this shape
   uint32_t stride;         // every stride-th 256-coordinate slice is sampled
   uint32_t target;         // sampled coordinates wanted at or above the lower bound
-  uint32_t cap;            // candidate list capacity per row
+  uint32_t cap;            // capacity of one candidate sub-list
   uint32_t nbk;            // 4096-coordinate buckets per row
   uint64_t words_per_row;  // bitmap words per row
 };
@@ -62,10 +62,9 @@ struct FastPlan {
 struct FastScratch {
   uint32_t* sample_hist;   // rows x 8192 (zero between calls)
   uint32_t* lower_key;     // rows
-  uint32_t* cand_cnt;      // rows
-  uint2* cand;             // rows x cap (index, value bits)
-  uint32_t* hist;          // rows x 2048 (zero between calls)
-  uint32_t* done;          // rows (zero between calls)
+  uint32_t* cand_cnt;      // rows x sub-lists, one counter per 128-byte line
+  uint2* cand;             // rows x sub-lists x cap (index, value bits)
+  uint32_t* hist;          // rows x fast_hist_blocks() x 2048 partial histograms
   void* sel;               // rows x fast_sel_bytes()
   uint32_t* need;          // rows: 1 = the dense path must redo this row
   uint32_t* bitmap;        // rows x words_per_row (zero between calls)
@@ -75,6 +74,9 @@ struct FastScratch {
 
 FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K);
 size_t fast_sel_bytes();
+uint32_t fast_sublists();
+uint32_t fast_counter_stride();
+uint32_t fast_hist_blocks();
 // Same contract as dense_select, except that rows whose need flag is set on return are
 // left unselected (x already holds fma(alpha, g, x) for every row).
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,

@@ -26,17 +26,19 @@ template <int DIGIT, bool FMA>
 __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
                                                  float* __restrict__ x, uint64_t d, float alpha,
                                                  const SelState* __restrict__ st,
-                                                 uint32_t* __restrict__ hist, RowMask need) {
+                                                 uint32_t* __restrict__ hist, uint32_t nwc,
+                                                 RowMask need) {
   constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
   __shared__ uint32_t sh[NB];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
   for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
   __syncthreads();
-  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  const ChunkGeom c = wave_chunk(d, row, wc);
   const uint32_t prefix = DIGIT == 0 ? 0u : st[row].prefix;
-  if (c.active) {
+  for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
+       wc += gridDim.x * kWavesPerBlock) {
+    const ChunkGeom c = wave_chunk(d, row, wc);
+    if (!c.active) break;
     visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t, const float (&v)[4], uint32_t mask) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -115,10 +117,10 @@ __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, u
                                                   RowMask need) {
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
-  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  if (wc >= nwc) return;
-  const ChunkGeom c = wave_chunk(d, row, wc);
   const uint32_t T = st[row].T;
+  for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
+       wc += gridDim.x * kWavesPerBlock) {
+  const ChunkGeom c = wave_chunk(d, row, wc);
   uint32_t gt = 0, eq = 0;
   if (c.active) {
     visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f,
@@ -137,6 +139,7 @@ __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, u
   if (lane_id() == 0) {
     cnt_gt[(uint64_t)row * nwc + wc] = gt;
     cnt_eq[(uint64_t)row * nwc + wc] = eq;
+  }
   }
 }
 
@@ -178,11 +181,11 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
                                                  float* __restrict__ out_val, RowMask need) {
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
-  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  if (wc >= nwc) return;
-  const ChunkGeom c = wave_chunk(d, row, wc);
-  if (!c.active) return;
   const uint32_t T = st[row].T, r = st[row].r;
+  for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
+       wc += gridDim.x * kWavesPerBlock) {
+  const ChunkGeom c = wave_chunk(d, row, wc);
+  if (!c.active) break;
   uint32_t run_gt = off_gt[(uint64_t)row * nwc + wc];   // wave-uniform running counts
   uint32_t run_eq = off_eq[(uint64_t)row * nwc + wc];
   uint32_t* oi = out_idx + (uint64_t)row * K;
@@ -217,6 +220,7 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
     run_gt += tot_gt;
     run_eq += tot_eq;
   });
+  }
 }
 
 // x = fma(alpha, g, x) with no selection (K == 0).
@@ -263,7 +267,15 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
                         float* out_val, RowMask need, bool first_pass_done,
                         hipEvent_t ev0, hipEvent_t ev1) {
   const uint32_t nwc = sc.nwc;
-  const dim3 grid((nwc + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  // One wave per chunk when the path is the primary one.  As a gated fallback most rows
+  // leave at once, so a small grid whose blocks loop over the chunks keeps the cost of
+  // the idle launches down.
+  uint32_t gx = (nwc + kWavesPerBlock - 1) / kWavesPerBlock;
+  if (need != nullptr) {
+    const uint32_t lim = rows >= 4096 ? 1u : 4096u / rows;
+    if (gx > lim) gx = lim;
+  }
+  const dim3 grid(gx, rows);
   const dim3 block(kBlock);
   hipError_t e = fill_u32(s, sc.hist, (uint64_t)rows * kBins0, 0);
   if (e != hipSuccess) return e;
@@ -271,20 +283,20 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   const bool fuse = (g != nullptr) && !first_pass_done;
   if (fuse) {
     if (ev0) (void)hipEventRecord(ev0, s);
-    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, sc.state, sc.hist, need);
+    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, sc.state, sc.hist, nwc, need);
     BTS_LAUNCH_CHECK();
     if (ev1) (void)hipEventRecord(ev1, s);
   } else {
-    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, need);
+    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, nwc, need);
     BTS_LAUNCH_CHECK();
   }
   k_scan_digit<0><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
   BTS_LAUNCH_CHECK();
-  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, need);
+  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, nwc, need);
   BTS_LAUNCH_CHECK();
   k_scan_digit<1><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
   BTS_LAUNCH_CHECK();
-  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, need);
+  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, nwc, need);
   BTS_LAUNCH_CHECK();
   k_scan_digit<2><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
   BTS_LAUNCH_CHECK();

@@ -35,10 +35,13 @@ constexpr int kSampleBins = 1 << kSampleBits;         // 8192
 constexpr int kSampleShift = 31 - kSampleBits;        // 18
 constexpr uint32_t kSlice = kWave * 4;                // 256 coordinates: one f4 per lane
 constexpr int kSliceUnroll = 8;
-
-__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// The candidate list of a row is kept as kSubLists independent sub-lists, each with its own
+// append counter on its own 128-byte line: appends to one address serialise in L2 at a few
+// million per second, far too slow for one counter per row.  Wave-chunk wc appends to
+// sub-list wc % kSubLists, which spreads even clustered hits evenly.
+constexpr uint32_t kSubLists = 64;
+constexpr uint32_t kCounterStride = 32;               // words between two counters
+constexpr uint32_t kMaxHistBlocks = 32;               // blocks per row in a candidate pass
 
 // ---- 1. sample histogram ------------------------------------------------------------
 // Slices are cut at absolute multiples of 256 coordinates (16-byte aligned); only slices
@@ -125,13 +128,17 @@ __global__ __launch_bounds__(kBlock) void k_pick_bound(uint32_t* __restrict__ sh
   }
   __syncthreads();
   for (int i = 0; i < BPT; ++i) h[top - i] = 0;
-  if (threadIdx.x == 0) {
-    lower_key[row] = s_bin << kSampleShift;
-    cand_cnt[row] = 0;
-  }
+  if (threadIdx.x == 0) lower_key[row] = s_bin << kSampleShift;
+  if (threadIdx.x < kSubLists)
+    cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride] = 0;
 }
 
 // ---- 2. the dense pass ------------------------------------------------------------------
+// One wave per kWaveChunk coordinates.  Whole chunks take the fast body: kUnroll 16-byte
+// loads per lane and array in flight, fused multiply-add, store, compare against the
+// row's lower bound; the lanes' hits (rare) are ranked with one wave scan and appended
+// with ONE atomic add per chunk (to the chunk's sub-list).  The partial chunks at the ends of a row go slice by
+// slice.
 template <bool FMA>
 __global__ __launch_bounds__(kBlock) void k_stream_capture(
     const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
@@ -142,8 +149,58 @@ __global__ __launch_bounds__(kBlock) void k_stream_capture(
   const ChunkGeom c = wave_chunk(d, row, wc);
   if (!c.active) return;
   const uint32_t L = lower_key[row];
-  uint2* list = cand + (uint64_t)row * cap;
-  uint32_t* counter = cand_cnt + row;
+  const uint64_t sub = (uint64_t)row * kSubLists + wc % kSubLists;
+  uint2* list = cand + sub * cap;                 // cap = capacity of one sub-list
+  uint32_t* counter = cand_cnt + sub * kCounterStride;
+  if (c.full) {
+    const uint64_t e0 = c.base + (uint64_t)lane_id() * 4;
+    f4 xv[kUnroll];
+    f4 gv[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t e = e0 + (uint64_t)u * (kWave * 4);
+      xv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(x + e));
+      if (FMA) gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
+    }
+    uint32_t flags = 0;                       // bit 4u + j: element j of slice u is a hit
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t e = e0 + (uint64_t)u * (kWave * 4);
+      if (FMA) {
+        xv[u].x = __fmaf_rn(alpha, gv[u].x, xv[u].x);
+        xv[u].y = __fmaf_rn(alpha, gv[u].y, xv[u].y);
+        xv[u].z = __fmaf_rn(alpha, gv[u].z, xv[u].z);
+        xv[u].w = __fmaf_rn(alpha, gv[u].w, xv[u].w);
+        __builtin_nontemporal_store(xv[u], reinterpret_cast<f4*>(x + e));
+      }
+      flags |= (key_of(xv[u].x) >= L ? 1u : 0u) << (4 * u);
+      flags |= (key_of(xv[u].y) >= L ? 2u : 0u) << (4 * u);
+      flags |= (key_of(xv[u].z) >= L ? 4u : 0u) << (4 * u);
+      flags |= (key_of(xv[u].w) >= L ? 8u : 0u) << (4 * u);
+    }
+    if (__ballot(flags != 0) == 0) return;
+    const uint32_t mine = __popc(flags);
+    const uint32_t incl = wave_inclusive_scan(mine);
+    const uint32_t total = __shfl(incl, kWave - 1, kWave);
+    uint32_t base = 0;
+    if (lane_id() == 0) base = atomicAdd(counter, total);
+    base = __shfl(base, 0, kWave);
+    uint32_t pos = base + incl - mine;
+    const uint32_t i0 = (uint32_t)(e0 - c.lo);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const float v[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (flags & (1u << (4 * u + j))) {
+          if (pos < cap)
+            list[pos] = make_uint2(i0 + (uint32_t)u * (kWave * 4) + j, __float_as_uint(v[j]));
+          ++pos;
+        }
+      }
+    }
+    return;
+  }
   visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t e, const float (&v)[4], uint32_t mask) {
     uint32_t flags = 0;
 #pragma unroll
@@ -174,65 +231,82 @@ struct FastSel {
   uint32_t I_T;               // ties with index <= I_T are kept
 };
 
+// Verify: the single pass succeeded for a row when no sub-list overflowed and the lists
+// together hold at least K coordinates (then the K largest of the row are all listed).
+__global__ __launch_bounds__(kWave) void k_cand_check(const uint32_t* __restrict__ cand_cnt,
+                                                      uint32_t cap, uint32_t K,
+                                                      uint32_t* __restrict__ need) {
+  const uint32_t row = blockIdx.x;
+  const uint32_t c = cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride];
+  const uint32_t total = wave_sum(c);
+  const bool over = __ballot(c > cap) != 0;
+  if (threadIdx.x == 0) need[row] = (over || total < K) ? 1u : 0u;
+}
+
 // PASS 0..2: digits of the key (descending).  PASS 3..5: digits of the index among the
 // coordinates whose key equals T (ascending), run only when ties must be split.
-// Several blocks per row histogram their share of the list; the block that finishes
-// last (ticket counter) walks the histogram and advances the row's state.
+// A pass is two kernels: k_cand_hist (a few blocks per row, each histogramming whole
+// sub-lists in LDS and storing its partial histogram with plain stores) and k_cand_scan
+// (one block per row: adds the partials, walks the bins, advances the row's state).  No
+// cross-block atomics or fences: on this part they are served at the memory side and
+// same-address traffic serialises.
 template <int PASS>
-__global__ __launch_bounds__(kBlock) void k_cand_pass(const uint2* __restrict__ cand,
+__global__ __launch_bounds__(kBlock) void k_cand_hist(const uint2* __restrict__ cand,
                                                       const uint32_t* __restrict__ cand_cnt,
-                                                      uint32_t cap, uint32_t K,
-                                                      uint32_t* __restrict__ hist,
-                                                      uint32_t* __restrict__ done,
-                                                      FastSel* __restrict__ sel,
-                                                      uint32_t* __restrict__ need) {
-  constexpr bool kOnIndex = PASS >= 3;
+                                                      uint32_t cap,
+                                                      uint32_t* __restrict__ partial,
+                                                      const FastSel* __restrict__ sel,
+                                                      const uint32_t* __restrict__ need) {
   constexpr int NB = (PASS == 0 || PASS == 3 || PASS == 4) ? 2048 : 1024;
-  constexpr int BPT = NB / kBlock;
   __shared__ uint32_t sh[NB];
-  __shared__ uint32_t lds[kBlock / kWave + 1];
-  __shared__ uint32_t s_ticket;
   const uint32_t row = blockIdx.y;
-  const uint32_t cnt = cand_cnt[row];
-  const bool valid = cnt >= K && cnt <= cap;
-  if (PASS == 0 && blockIdx.x == 0 && threadIdx.x == 0) need[row] = valid ? 0u : 1u;
-  if (!valid) return;
+  if (need[row]) return;
   FastSel s;
   if (PASS > 0) s = sel[row];
-  if (kOnIndex && s.r == s.eq_total) return;          // every tie is kept: nothing to split
+  if (PASS >= 3 && s.r == s.eq_total) return;         // every tie is kept: nothing to split
   for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
   __syncthreads();
-  const uint2* list = cand + (uint64_t)row * cap;
-  for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < cnt; j += gridDim.x * kBlock) {
-    const uint2 en = list[j];
-    const uint32_t idx = en.x, key = en.y & 0x7FFFFFFFu;
-    if (PASS == 0) {
-      atomicAdd(&sh[key >> 20], 1u);
-    } else if (PASS == 1) {
-      if ((key >> 20) == s.prefix) atomicAdd(&sh[(key >> 10) & 1023u], 1u);
-    } else if (PASS == 2) {
-      if ((key >> 10) == s.prefix) atomicAdd(&sh[key & 1023u], 1u);
-    } else if (PASS == 3) {
-      if (key == s.T) atomicAdd(&sh[idx >> 21], 1u);
-    } else if (PASS == 4) {
-      if (key == s.T && (idx >> 21) == s.iprefix) atomicAdd(&sh[(idx >> 10) & 2047u], 1u);
-    } else {
-      if (key == s.T && (idx >> 10) == s.iprefix) atomicAdd(&sh[idx & 1023u], 1u);
+  for (uint32_t sl = blockIdx.x; sl < kSubLists; sl += gridDim.x) {
+    const uint64_t sub = (uint64_t)row * kSubLists + sl;
+    const uint32_t cnt = cand_cnt[sub * kCounterStride];
+    const uint2* list = cand + sub * cap;
+    for (uint32_t j = threadIdx.x; j < cnt; j += kBlock) {
+      const uint2 en = list[j];
+      const uint32_t idx = en.x, key = en.y & 0x7FFFFFFFu;
+      if (PASS == 0) {
+        atomicAdd(&sh[key >> 20], 1u);
+      } else if (PASS == 1) {
+        if ((key >> 20) == s.prefix) atomicAdd(&sh[(key >> 10) & 1023u], 1u);
+      } else if (PASS == 2) {
+        if ((key >> 10) == s.prefix) atomicAdd(&sh[key & 1023u], 1u);
+      } else if (PASS == 3) {
+        if (key == s.T) atomicAdd(&sh[idx >> 21], 1u);
+      } else if (PASS == 4) {
+        if (key == s.T && (idx >> 21) == s.iprefix) atomicAdd(&sh[(idx >> 10) & 2047u], 1u);
+      } else {
+        if (key == s.T && (idx >> 10) == s.iprefix) atomicAdd(&sh[idx & 1023u], 1u);
+      }
     }
   }
   __syncthreads();
-  uint32_t* h = hist + (uint64_t)row * 2048;
-  for (int i = threadIdx.x; i < NB; i += kBlock) {
-    const uint32_t v = sh[i];
-    if (v) atomicAdd(&h[i], v);
-  }
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) s_ticket = atomicAdd(&done[row], 1u);
-  __syncthreads();
-  if (s_ticket != gridDim.x - 1) return;
+  uint32_t* out = partial + ((uint64_t)row * gridDim.x + blockIdx.x) * 2048;
+  for (int i = threadIdx.x; i < NB; i += kBlock) out[i] = sh[i];
+}
 
-  // Last block of the row: every block's counts are in h.
+template <int PASS>
+__global__ __launch_bounds__(kBlock) void k_cand_scan(const uint32_t* __restrict__ partial,
+                                                      uint32_t nparts, uint32_t K,
+                                                      FastSel* __restrict__ sel,
+                                                      const uint32_t* __restrict__ need) {
+  constexpr bool kOnIndex = PASS >= 3;
+  constexpr int NB = (PASS == 0 || PASS == 3 || PASS == 4) ? 2048 : 1024;
+  constexpr int BPT = NB / kBlock;
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  const uint32_t row = blockIdx.x;
+  if (need[row]) return;
+  FastSel s;
+  if (PASS > 0) s = sel[row];
+  if (kOnIndex && s.r == s.eq_total) return;
   const uint32_t want = PASS == 0 ? K : (kOnIndex ? s.i_rem : s.k_rem);
   // thread t owns BPT consecutive bins, walked from the end the select starts at
   const int start = kOnIndex ? (int)threadIdx.x * BPT : NB - 1 - (int)threadIdx.x * BPT;
@@ -240,15 +314,16 @@ __global__ __launch_bounds__(kBlock) void k_cand_pass(const uint2* __restrict__ 
   uint32_t c[BPT];
   uint32_t sum = 0;
 #pragma unroll
-  for (int i = 0; i < BPT; ++i) {
-    c[i] = ld_agent(&h[start + dir * i]);
-    sum += c[i];
+  for (int i = 0; i < BPT; ++i) c[i] = 0;
+  for (uint32_t b = 0; b < nparts; ++b) {
+    const uint32_t* h = partial + ((uint64_t)row * nparts + b) * 2048;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) c[i] += h[start + dir * i];
   }
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) sum += c[i];
   uint32_t total;
   const uint32_t excl = block_exclusive_scan(sum, lds, &total);
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) h[start + dir * i] = 0;
-  if (threadIdx.x == 0) done[row] = 0;
   if (excl < want && want <= excl + sum) {
     uint32_t acc = excl;
     int bin = start;
@@ -302,12 +377,14 @@ __global__ __launch_bounds__(kBlock) void k_mark(const uint2* __restrict__ cand,
                                                  uint32_t nbk) {
   const uint32_t row = blockIdx.y;
   if (need[row]) return;
-  const uint32_t cnt = cand_cnt[row];
   const uint32_t T = sel[row].T, I_T = sel[row].I_T;
-  const uint2* list = cand + (uint64_t)row * cap;
+  const uint64_t sub = (uint64_t)row * kSubLists + blockIdx.x % kSubLists;
+  const uint32_t cnt = cand_cnt[sub * kCounterStride];
+  const uint2* list = cand + sub * cap;
+  const uint32_t part = blockIdx.x / kSubLists, parts = gridDim.x / kSubLists;
   uint32_t* bm = bitmap + (uint64_t)row * words_per_row;
   uint32_t* bc = bucket_cnt + (uint64_t)row * nbk;
-  for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < cnt; j += gridDim.x * kBlock) {
+  for (uint32_t j = part * kBlock + threadIdx.x; j < cnt; j += parts * kBlock) {
     const uint2 en = list[j];
     const uint32_t idx = en.x, key = en.y & 0x7FFFFFFFu;
     if (key > T || (key == T && idx <= I_T)) {
@@ -338,7 +415,9 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(const uint32_t* __restrict
   }
 }
 
-// One wave per non-empty bucket: lane l owns bitmap words 2l and 2l+1 of the bucket.
+// One wave per group of 64 buckets: the lanes fetch the 64 counters at once, and the wave
+// then walks the non-empty buckets of its group; inside a bucket lane l owns bitmap words
+// 2l and 2l+1.
 __global__ __launch_bounds__(kBlock) void k_emit_bitmap(
     float* __restrict__ x, uint64_t d, uint32_t K, uint32_t* __restrict__ bitmap,
     uint64_t words_per_row, uint32_t* __restrict__ bucket_cnt,
@@ -346,39 +425,47 @@ __global__ __launch_bounds__(kBlock) void k_emit_bitmap(
     uint32_t* __restrict__ out_idx, float* __restrict__ out_val) {
   const uint32_t row = blockIdx.y;
   if (need[row]) return;
-  const uint32_t bk = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  if (bk >= nbk) return;
+  const uint32_t group = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  const uint32_t bk_mine = group * kWave + lane_id();
   uint32_t* bc = bucket_cnt + (uint64_t)row * nbk;
-  if (bc[bk] == 0) return;                                   // wave-uniform
+  const uint32_t my_cnt = bk_mine < nbk ? bc[bk_mine] : 0u;
+  uint64_t live = __ballot(my_cnt != 0);
+  if (live == 0) return;
+  const uint32_t my_off = my_cnt ? bucket_off[(uint64_t)row * nbk + bk_mine] : 0u;
+  if (my_cnt) bc[bk_mine] = 0;
   uint32_t* bm = bitmap + (uint64_t)row * words_per_row;
-  const uint64_t w0 = (uint64_t)bk * kBucketWords + 2u * lane_id();
-  uint32_t a = 0, b = 0;
-  if (w0 < words_per_row) a = bm[w0];
-  if (w0 + 1 < words_per_row) b = bm[w0 + 1];
-  const uint32_t mine = __popc(a) + __popc(b);
-  uint32_t pos = bucket_off[(uint64_t)row * nbk + bk] + wave_inclusive_scan(mine) - mine;
   float* xr = x + (uint64_t)row * d;
   uint32_t* oi = out_idx + (uint64_t)row * K;
   float* ov = out_val + (uint64_t)row * K;
+  while (live) {
+    const int src = __ffsll((unsigned long long)live) - 1;
+    live &= live - 1;
+    const uint32_t bk = group * kWave + src;
+    const uint64_t w0 = (uint64_t)bk * kBucketWords + 2u * lane_id();
+    uint32_t a = 0, b = 0;
+    if (w0 < words_per_row) a = bm[w0];
+    if (w0 + 1 < words_per_row) b = bm[w0 + 1];
+    const uint32_t mine = __popc(a) + __popc(b);
+    uint32_t pos = __shfl(my_off, src, kWave) + wave_inclusive_scan(mine) - mine;
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    uint32_t bits = half == 0 ? a : b;
-    const uint32_t base = (uint32_t)((w0 + half) * 32u);
-    while (bits) {
-      const uint32_t t = __ffs(bits) - 1;
-      bits &= bits - 1;
-      const uint32_t idx = base + t;
-      if (pos < K && idx < d) {
-        oi[pos] = idx;
-        ov[pos] = xr[idx];
-        xr[idx] = 0.0f;
+    for (int half = 0; half < 2; ++half) {
+      uint32_t bits = half == 0 ? a : b;
+      const uint32_t base = (uint32_t)((w0 + half) * 32u);
+      while (bits) {
+        const uint32_t t = __ffs(bits) - 1;
+        bits &= bits - 1;
+        const uint32_t idx = base + t;
+        if (pos < K && idx < d) {
+          oi[pos] = idx;
+          ov[pos] = xr[idx];
+          xr[idx] = 0.0f;
+        }
+        ++pos;
       }
-      ++pos;
     }
+    if (a) bm[w0] = 0;
+    if (b) bm[w0 + 1] = 0;
   }
-  if (a) bm[w0] = 0;
-  if (b) bm[w0 + 1] = 0;
-  if (lane_id() == 0) bc[bk] = 0;
 }
 
 #define BTS_LAUNCH_CHECK()                       \
@@ -405,8 +492,9 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   if (stride < 1) stride = 1;
   uint64_t target = (2ull * K + stride - 1) / stride;
   if (target < 48) target = 48;
-  uint64_t cap = 4 * target * stride + 4096;
-  if (cap > d) cap = d;
+  // expected list length is 2K..4K (the bound is a histogram bin edge); each of the 64
+  // sub-lists gets twice its even share of 4x the target plus slack
+  uint64_t cap = (4 * target * stride + 4096) / 64 * 2 + 64;
   p.enabled = true;
   p.stride = (uint32_t)stride;
   p.target = (uint32_t)target;
@@ -447,31 +535,37 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   BTS_LAUNCH_CHECK();
   if (ev1) (void)hipEventRecord(ev1, s);
   // 3 + 4. verify and select
-  uint32_t cb = (pl.cap + 2047) / 2048;
-  if (cb > 128) cb = 128;
-  const dim3 cgrid(cb, rows);
+  // a few blocks per row, each taking whole sub-lists (about 4096 entries per block)
+  uint32_t hb = (uint32_t)(((uint64_t)pl.cap * kSubLists / 2 + 4095) / 4096);
+  if (hb > kMaxHistBlocks) hb = kMaxHistBlocks;
+  if (hb < 1) hb = 1;
+  const dim3 hgrid(hb, rows);
   FastSel* sel = reinterpret_cast<FastSel*>(sc.sel);
-  k_cand_pass<0><<<cgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sc.done, sel, sc.need);
+  k_cand_check<<<dim3(rows), dim3(kWave), 0, s>>>(sc.cand_cnt, pl.cap, K, sc.need);
   BTS_LAUNCH_CHECK();
-  k_cand_pass<1><<<cgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sc.done, sel, sc.need);
+#define BTS_CAND_PASS(P)                                                                       \
+  k_cand_hist<P><<<hgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, sc.hist, sel, sc.need); \
+  BTS_LAUNCH_CHECK();                                                                          \
+  k_cand_scan<P><<<dim3(rows), block, 0, s>>>(sc.hist, hb, K, sel, sc.need);                   \
   BTS_LAUNCH_CHECK();
-  k_cand_pass<2><<<cgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sc.done, sel, sc.need);
-  BTS_LAUNCH_CHECK();
-  k_cand_pass<3><<<cgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sc.done, sel, sc.need);
-  BTS_LAUNCH_CHECK();
-  k_cand_pass<4><<<cgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sc.done, sel, sc.need);
-  BTS_LAUNCH_CHECK();
-  k_cand_pass<5><<<cgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sc.done, sel, sc.need);
-  BTS_LAUNCH_CHECK();
+  BTS_CAND_PASS(0)
+  BTS_CAND_PASS(1)
+  BTS_CAND_PASS(2)
+  BTS_CAND_PASS(3)
+  BTS_CAND_PASS(4)
+  BTS_CAND_PASS(5)
+#undef BTS_CAND_PASS
   // 5. emit
-  uint32_t mb = (pl.cap + kBlock * 4 - 1) / (kBlock * 4);
-  if (mb > 256) mb = 256;
-  k_mark<<<dim3(mb, rows), block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, sel, sc.need, sc.bitmap,
+  uint32_t parts = (pl.cap + 2047) / 2048;            // blocks per sub-list
+  if (parts > 4) parts = 4;
+  if (parts < 1) parts = 1;
+  k_mark<<<dim3(kSubLists * parts, rows), block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, sel, sc.need, sc.bitmap,
                                           pl.words_per_row, sc.bucket_cnt, pl.nbk);
   BTS_LAUNCH_CHECK();
   k_bucket_scan<<<dim3(rows), dim3(1024), 0, s>>>(sc.bucket_cnt, sc.bucket_off, pl.nbk, sc.need);
   BTS_LAUNCH_CHECK();
-  k_emit_bitmap<<<dim3((pl.nbk + kWavesPerBlock - 1) / kWavesPerBlock, rows), block, 0, s>>>(
+  const uint32_t groups = (pl.nbk + kWave - 1) / kWave;
+  k_emit_bitmap<<<dim3((groups + kWavesPerBlock - 1) / kWavesPerBlock, rows), block, 0, s>>>(
       x, d, K, sc.bitmap, pl.words_per_row, sc.bucket_cnt, sc.bucket_off, pl.nbk, sc.need,
       out_idx, out_val);
   BTS_LAUNCH_CHECK();
@@ -479,5 +573,8 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
 }
 
 size_t fast_sel_bytes() { return sizeof(FastSel); }
+uint32_t fast_sublists() { return kSubLists; }
+uint32_t fast_counter_stride() { return kCounterStride; }
+uint32_t fast_hist_blocks() { return kMaxHistBlocks; }
 
 }  // namespace bts
