@@ -59,7 +59,13 @@ def main() -> int:
                     help="distinct gradient batches kept in HBM (0 = as many as steps+warmup, "
                          "capped by memory)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain copy kernel of known size (2^28 floats read, 2^28 "
+                         "written) so that a counter profile of this command can be scaled")
     ap.add_argument("--cpu-rows", type=int, default=0)
+    ap.add_argument("--path", choices=["auto", "dense", "single"], default="auto",
+                    help="select path: chosen by shape (default), dense multi-pass only, or "
+                         "single-pass wherever the shape allows")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -93,6 +99,7 @@ def main() -> int:
     torch.cuda.synchronize()
 
     ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn)
+    ctx.set_path({"auto": 0, "dense": 1, "single": 2}[args.path])
     eps = torch.zeros((N, d), dtype=torch.float32, device=dev)
     delta = torch.zeros(d, dtype=torch.float32, device=dev)
     w = wl.weights0(cfg, dev)
@@ -105,6 +112,13 @@ def main() -> int:
     def step(i):
         bts.bidir_step(ctx, ring[i % n_buf], eps, delta, w, p, cfg.alpha, 1.0, up_idx, up_val,
                        dn_idx, dn_val, None)
+
+    if args.calibrate_copy:
+        src_c = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst_c = torch.empty_like(src_c)
+        torch.mul(src_c, 1.0, out=dst_c)        # one elementwise kernel: 1 GiB in, 1 GiB out
+        torch.cuda.synchronize()
+        del src_c, dst_c
 
     it = 0
     for _ in range(args.warmup):
@@ -159,7 +173,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: N={N} workers, d={d}, K_up={cfg.K_up}, "
                                f"K_dn={cfg.K_dn}, {cfg.dist} gradients, fresh batch per step "
                                f"({n_buf} batches resident), residuals carried",
-                   "alpha_in": cfg.alpha, "alpha_out": 1.0,
+                   "alpha_in": cfg.alpha, "alpha_out": 1.0, "select_path": args.path,
                    "uplink_rows_single_pass": rows_fast, "uplink_rows_dense": rows_dense},
         "hbm_gbps_algorithmic": b_alg / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac_algorithmic": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
