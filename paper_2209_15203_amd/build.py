@@ -25,7 +25,8 @@ def sources():
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-I", os.path.join(HERE, "..", "include"), "-o", LIB] + sources()
+    extra = os.environ.get("BTS_DEFS", "").split()      # e.g. "-DBTS_UNROLL=2" for experiments
+    cmd = [hipcc] + FLAGS + extra + ["-I", os.path.join(HERE, "..", "include"), "-o", LIB] + sources()
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

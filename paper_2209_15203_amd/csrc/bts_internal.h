@@ -9,9 +9,17 @@ namespace bts {
 constexpr int kWave = 64;                 // CDNA wavefront
 constexpr int kBlock = 256;               // threads per workgroup in the dense passes
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kUnroll = 4;                // float4 loads in flight per lane and array
+#ifndef BTS_UNROLL
+#define BTS_UNROLL 2
+#endif
+#ifndef BTS_STREAM_BLOCK
+#define BTS_STREAM_BLOCK 128
+#endif
+constexpr int kUnroll = BTS_UNROLL;       // float4 loads in flight per lane and array
+constexpr int kStreamBlock = BTS_STREAM_BLOCK;   // threads per workgroup of the dominant kernel
+constexpr int kStreamWaves = kStreamBlock / kWave;
 // A wave owns kWaveChunk consecutive coordinates (absolute, 16-byte aligned offsets).
-constexpr uint32_t kWaveChunk = kWave * 4 * kUnroll;   // 1024
+constexpr uint32_t kWaveChunk = kWave * 4 * kUnroll;   
 constexpr int kBins0 = 2048;              // first digit: key bits 30..20
 constexpr int kBinsLo = 1024;             // second and third digit: bits 19..10, 9..0
 

@@ -140,12 +140,12 @@ __global__ __launch_bounds__(kBlock) void k_pick_bound(uint32_t* __restrict__ sh
 // with ONE atomic add per chunk (to the chunk's sub-list).  The partial chunks at the ends of a row go slice by
 // slice.
 template <bool FMA>
-__global__ __launch_bounds__(kBlock) void k_stream_capture(
+__global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
     const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
     const uint32_t* __restrict__ lower_key, uint32_t* __restrict__ cand_cnt,
     uint2* __restrict__ cand, uint32_t cap) {
   const uint32_t row = blockIdx.y;
-  const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  const uint32_t wc = blockIdx.x * kStreamWaves + threadIdx.x / kWave;
   const ChunkGeom c = wave_chunk(d, row, wc);
   if (!c.active) return;
   const uint32_t L = lower_key[row];
@@ -509,7 +509,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1) {
   const dim3 block(kBlock);
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
-  const dim3 dense_grid((nwc + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  const dim3 dense_grid((nwc + kStreamWaves - 1) / kStreamWaves, rows);
   // 1. sample
   const uint64_t n_samp = (d / 256) / pl.stride + 1;
   uint32_t sample_blocks = (uint32_t)((n_samp + kWavesPerBlock * 8 - 1) / (kWavesPerBlock * 8));
@@ -527,10 +527,10 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   // 2. the dense pass
   if (ev0) (void)hipEventRecord(ev0, s);
   if (g != nullptr)
-    k_stream_capture<true><<<dense_grid, block, 0, s>>>(g, x, d, alpha, sc.lower_key, sc.cand_cnt,
+    k_stream_capture<true><<<dense_grid, dim3(kStreamBlock), 0, s>>>(g, x, d, alpha, sc.lower_key, sc.cand_cnt,
                                                         sc.cand, pl.cap);
   else
-    k_stream_capture<false><<<dense_grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.lower_key,
+    k_stream_capture<false><<<dense_grid, dim3(kStreamBlock), 0, s>>>(nullptr, x, d, 0.0f, sc.lower_key,
                                                          sc.cand_cnt, sc.cand, pl.cap);
   BTS_LAUNCH_CHECK();
   if (ev1) (void)hipEventRecord(ev1, s);
