@@ -20,6 +20,7 @@ struct bts_ctx {
   DenseScratch dense;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
+  uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
   std::vector<void*> owned;     // every device allocation of the context
   // timing of the dominant kernel
   bool profile;
@@ -149,6 +150,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->dense = DenseScratch{};
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
+  ctx->agg_ranges = nullptr;
   if (hipGetDevice(&ctx->device) != hipSuccess) {
     delete ctx;
     return BTS_EHIP;
@@ -162,6 +164,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
             dev_alloc(ctx, &ctx->dense.state, (size_t)rows) &&
             dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
+            dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_ranges(d)) &&
             alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up) &&
             alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn);
   if (!ok) {
@@ -193,7 +196,7 @@ int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, 
   if (!ctx || !p || !delta) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
   hipError_t e = aggregate(ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, delta,
-                           ctx->d, union_nnz);
+                           ctx->d, union_nnz, ctx->agg_ranges);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 

@@ -415,9 +415,11 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(const uint32_t* __restrict
   }
 }
 
-// One wave per group of 64 buckets: the lanes fetch the 64 counters at once, and the wave
-// then walks the non-empty buckets of its group; inside a bucket lane l owns bitmap words
-// 2l and 2l+1.
+// One wave per group of GROUP consecutive buckets (GROUP = 1, 8 or 64, chosen so that the
+// launch has enough waves): the first GROUP lanes fetch the group's counters at once and
+// the wave then walks its non-empty buckets; inside a bucket lane l owns bitmap words 2l
+// and 2l+1.
+template <int GROUP>
 __global__ __launch_bounds__(kBlock) void k_emit_bitmap(
     float* __restrict__ x, uint64_t d, uint32_t K, uint32_t* __restrict__ bitmap,
     uint64_t words_per_row, uint32_t* __restrict__ bucket_cnt,
@@ -426,9 +428,9 @@ __global__ __launch_bounds__(kBlock) void k_emit_bitmap(
   const uint32_t row = blockIdx.y;
   if (need[row]) return;
   const uint32_t group = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  const uint32_t bk_mine = group * kWave + lane_id();
+  const uint32_t bk_mine = group * GROUP + lane_id();
   uint32_t* bc = bucket_cnt + (uint64_t)row * nbk;
-  const uint32_t my_cnt = bk_mine < nbk ? bc[bk_mine] : 0u;
+  const uint32_t my_cnt = (lane_id() < GROUP && bk_mine < nbk) ? bc[bk_mine] : 0u;
   uint64_t live = __ballot(my_cnt != 0);
   if (live == 0) return;
   const uint32_t my_off = my_cnt ? bucket_off[(uint64_t)row * nbk + bk_mine] : 0u;
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(kBlock) void k_emit_bitmap(
   while (live) {
     const int src = __ffsll((unsigned long long)live) - 1;
     live &= live - 1;
-    const uint32_t bk = group * kWave + src;
+    const uint32_t bk = group * GROUP + src;
     const uint64_t w0 = (uint64_t)bk * kBucketWords + 2u * lane_id();
     uint32_t a = 0, b = 0;
     if (w0 < words_per_row) a = bm[w0];
@@ -564,10 +566,20 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   BTS_LAUNCH_CHECK();
   k_bucket_scan<<<dim3(rows), dim3(1024), 0, s>>>(sc.bucket_cnt, sc.bucket_off, pl.nbk, sc.need);
   BTS_LAUNCH_CHECK();
-  const uint32_t groups = (pl.nbk + kWave - 1) / kWave;
-  k_emit_bitmap<<<dim3((groups + kWavesPerBlock - 1) / kWavesPerBlock, rows), block, 0, s>>>(
-      x, d, K, sc.bitmap, pl.words_per_row, sc.bucket_cnt, sc.bucket_off, pl.nbk, sc.need,
-      out_idx, out_val);
+  // enough waves to fill the chip, few enough that empty groups stay cheap
+  const uint64_t buckets = (uint64_t)rows * pl.nbk;
+  const int group = buckets >= (64ull << 17) ? 64 : (buckets >= (8ull << 17) ? 8 : 1);
+  const uint32_t groups = (pl.nbk + group - 1) / group;
+  const dim3 egrid((groups + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  if (group == 64)
+    k_emit_bitmap<64><<<egrid, block, 0, s>>>(x, d, K, sc.bitmap, pl.words_per_row, sc.bucket_cnt,
+                                              sc.bucket_off, pl.nbk, sc.need, out_idx, out_val);
+  else if (group == 8)
+    k_emit_bitmap<8><<<egrid, block, 0, s>>>(x, d, K, sc.bitmap, pl.words_per_row, sc.bucket_cnt,
+                                             sc.bucket_off, pl.nbk, sc.need, out_idx, out_val);
+  else
+    k_emit_bitmap<1><<<egrid, block, 0, s>>>(x, d, K, sc.bitmap, pl.words_per_row, sc.bucket_cnt,
+                                             sc.bucket_off, pl.nbk, sc.need, out_idx, out_val);
   BTS_LAUNCH_CHECK();
   return hipSuccess;
 }

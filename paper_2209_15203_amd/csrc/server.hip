@@ -3,11 +3,13 @@
 // and the model update  w_t = w_{t-1} - Top_K(g_t)  on the received pairs.
 //
 // Aggregation is deterministic without float atomics: the coordinate axis is cut into
-// ranges, one workgroup owns a range, and inside it the workers are applied one after
-// the other in ascending q (a worker never names a coordinate twice, so the pairs of one
-// worker are applied in parallel; a workgroup barrier separates consecutive workers).
-// Each worker's pairs that fall into the range are found by binary search in its sorted
-// index list.
+// ranges of kAggWidth coordinates, one workgroup owns a range, and inside it the workers
+// are applied one after the other in ascending q (a worker never names a coordinate twice,
+// so the pairs of one worker are applied in parallel; a workgroup barrier separates
+// consecutive workers).  Each worker's pairs that fall into the range are found by binary
+// search in its sorted index list.  The range's pairs are staged in LDS and the touched
+// part of delta is gathered into an LDS accumulator first, so that the N dependent
+// rounds run at LDS latency instead of HBM latency.
 
 #include "bts_device.h"
 
@@ -16,7 +18,9 @@ namespace bts {
 namespace {
 
 constexpr int kAggBlock = 256;
-constexpr int kAggTile = 256;   // workers whose range bounds are held in LDS at a time
+constexpr int kAggTile = 256;          // workers whose range bounds are held in LDS at a time
+constexpr uint32_t kAggWidth = 4096;   // coordinates per range
+constexpr uint32_t kAggStage = 1024;   // pairs staged in LDS at a time
 
 __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__ a, uint32_t n,
                                                     uint32_t key) {
@@ -30,53 +34,103 @@ __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__
 
 __global__ __launch_bounds__(kAggBlock) void k_aggregate(
     const uint32_t* __restrict__ up_idx, const float* __restrict__ up_val,
-    const float* __restrict__ p, uint32_t N, uint32_t K_up, float* delta, uint64_t d,
-    uint32_t width, uint32_t* __restrict__ union_nnz) {
-  extern __shared__ uint32_t touched[];              // width / 32 words
-  __shared__ uint32_t s_lo[kAggTile], s_hi[kAggTile];
-  __shared__ uint32_t s_new;
-  const uint64_t c0 = (uint64_t)blockIdx.x * width;
-  const uint64_t c1 = min(c0 + (uint64_t)width, d);
-  const uint32_t words = width / 32;
-  for (uint32_t i = threadIdx.x; i < words; i += kAggBlock) touched[i] = 0;
-  if (threadIdx.x == 0) s_new = 0;
+    const float* __restrict__ p, uint32_t N, uint32_t K_up, float* __restrict__ delta,
+    uint64_t d, uint32_t* __restrict__ range_nnz) {
+  __shared__ float acc[kAggWidth];                  // g_t of the touched coordinates
+  __shared__ uint32_t touched[kAggWidth / 32];
+  __shared__ uint32_t s_lo[kAggTile], s_pref[kAggTile + 1];
+  __shared__ float s_p[kAggTile];
+  __shared__ uint32_t e_rel[kAggStage];
+  __shared__ float e_val[kAggStage];
+  __shared__ uint32_t lds[kAggBlock / kWave + 1];
+  const uint64_t c0 = (uint64_t)blockIdx.x * kAggWidth;
+  const uint64_t c1 = min(c0 + (uint64_t)kAggWidth, d);
+  for (uint32_t i = threadIdx.x; i < kAggWidth / 32; i += kAggBlock) touched[i] = 0;
   uint32_t fresh = 0;
   for (uint32_t q0 = 0; q0 < N; q0 += kAggTile) {
-    __syncthreads();
     const uint32_t nq = min((uint32_t)kAggTile, N - q0);
+    // where each worker of the tile enters and leaves the range
+    uint32_t lo = 0, n = 0;
     if (threadIdx.x < nq) {
       const uint32_t* row = up_idx + (uint64_t)(q0 + threadIdx.x) * K_up;
-      s_lo[threadIdx.x] = lower_bound_u32(row, K_up, (uint32_t)c0);
-      // c1 <= d < 2^32 except that c1 == 2^32 cannot occur (d < 2^32)
-      s_hi[threadIdx.x] = lower_bound_u32(row, K_up, (uint32_t)c1);
+      lo = lower_bound_u32(row, K_up, (uint32_t)c0);
+      n = lower_bound_u32(row, K_up, (uint32_t)c1) - lo;   // c1 <= d < 2^32
+      s_p[threadIdx.x] = p[q0 + threadIdx.x];
     }
+    uint32_t total;
+    const uint32_t pref = block_exclusive_scan(n, lds, &total);   // barriers inside
+    s_lo[threadIdx.x] = lo;
+    s_pref[threadIdx.x] = pref;
+    if (threadIdx.x == kAggBlock - 1) s_pref[kAggTile] = total;
     __syncthreads();
-    for (uint32_t t = 0; t < nq; ++t) {
-      const uint32_t lo = s_lo[t], hi = s_hi[t];
-      if (hi <= lo) continue;                        // uniform over the block
-      const uint32_t q = q0 + t;
-      const float pq = p[q];
-      const uint32_t* row_i = up_idx + (uint64_t)q * K_up;
-      const float* row_v = up_val + (uint64_t)q * K_up;
-      for (uint32_t j = lo + threadIdx.x; j < hi; j += kAggBlock) {
-        const uint32_t i = row_i[j];
-        if (i >= c0 && i < c1) {                     // always true for sorted input
-          delta[i] = __fmaf_rn(pq, row_v[j], delta[i]);
-          const uint32_t rel = i - (uint32_t)c0;
+    // the tile's pairs in (q, index) order, kAggStage at a time
+    uint32_t t_first = 0;                                   // first worker of the stage
+    for (uint32_t e0 = 0; e0 < total; e0 += kAggStage) {
+      const uint32_t e1 = min(e0 + kAggStage, total);
+      for (uint32_t e = e0 + threadIdx.x; e < e1; e += kAggBlock) {
+        // worker of pair e: the last t with s_pref[t] <= e
+        uint32_t a = 0, b = nq;
+        while (b - a > 1) {
+          const uint32_t m = (a + b) >> 1;
+          if (s_pref[m] <= e) a = m; else b = m;
+        }
+        const uint64_t src = (uint64_t)(q0 + a) * K_up + s_lo[a] + (e - s_pref[a]);
+        const uint32_t i = up_idx[src];
+        uint32_t rel = 0xFFFFFFFFu;
+        if (i >= c0 && i < c1) {                             // always true for sorted input
+          rel = i - (uint32_t)c0;
           const uint32_t bit = 1u << (rel & 31);
           const uint32_t old = atomicOr(&touched[rel >> 5], bit);
-          fresh += (old & bit) ? 0u : 1u;
+          if (!(old & bit)) {                                // first touch: fetch delta
+            acc[rel] = delta[i];
+            ++fresh;
+          }
         }
+        e_rel[e - e0] = rel;
+        e_val[e - e0] = up_val[src];
       }
-      __syncthreads();                               // next worker may name the same i
+      __syncthreads();
+      // one round per worker present in the stage, in ascending q
+      while (t_first + 1 < nq && s_pref[t_first + 1] <= e0) ++t_first;
+      for (uint32_t t = t_first; t < nq && s_pref[t] < e1; ++t) {
+        const uint32_t a = max(s_pref[t], e0), b = min(s_pref[t + 1], e1);
+        if (b <= a) continue;                                // uniform over the block
+        const float pq = s_p[t];
+        for (uint32_t e = a + threadIdx.x; e < b; e += kAggBlock) {
+          const uint32_t rel = e_rel[e - e0];
+          if (rel != 0xFFFFFFFFu) acc[rel] = __fmaf_rn(pq, e_val[e - e0], acc[rel]);
+        }
+        __syncthreads();                                     // next worker may name the same i
+      }
+    }
+    __syncthreads();
+  }
+  // write the touched coordinates back
+  for (uint32_t w = threadIdx.x; w < kAggWidth / 32; w += kAggBlock) {
+    uint32_t bits = touched[w];
+    while (bits) {
+      const uint32_t t = __ffs(bits) - 1;
+      bits &= bits - 1;
+      const uint32_t rel = w * 32 + t;
+      delta[c0 + rel] = acc[rel];
     }
   }
-  if (union_nnz != nullptr) {
-    fresh = wave_sum(fresh);
-    if (lane_id() == 0 && fresh) atomicAdd(&s_new, fresh);
-    __syncthreads();
-    if (threadIdx.x == 0 && s_new) atomicAdd(union_nnz, s_new);
+  if (range_nnz != nullptr) {
+    uint32_t total;
+    (void)block_exclusive_scan(fresh, lds, &total);
+    if (threadIdx.x == 0) range_nnz[blockIdx.x] = total;
   }
+}
+
+// Sum of the per-range counts of distinct coordinates: one block.
+__global__ __launch_bounds__(1024) void k_sum_ranges(const uint32_t* __restrict__ v, uint32_t n,
+                                                     uint32_t* __restrict__ out) {
+  __shared__ uint32_t lds[1024 / kWave + 1];
+  uint32_t s = 0;
+  for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s += v[i];
+  uint32_t total;
+  (void)block_exclusive_scan(s, lds, &total);
+  if (threadIdx.x == 0) *out = total;
 }
 
 __global__ void k_update(const uint32_t* __restrict__ idx, const float* __restrict__ val,
@@ -90,21 +144,21 @@ __global__ void k_update(const uint32_t* __restrict__ idx, const float* __restri
 
 }  // namespace
 
+uint32_t aggregate_ranges(uint64_t d) { return (uint32_t)((d + kAggWidth - 1) / kAggWidth); }
+
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
-                     uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz) {
-  if (union_nnz != nullptr) {
-    hipError_t e = fill_u32(s, union_nnz, 1, 0);
-    if (e != hipSuccess) return e;
+                     uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
+                     uint32_t* range_scratch) {
+  if (K_up == 0) {
+    if (union_nnz != nullptr) return fill_u32(s, union_nnz, 1, 0);
+    return hipSuccess;
   }
-  if (K_up == 0) return hipSuccess;
-  // Range width: a multiple of 32 coordinates, at most 16384 ranges, at least 1024 wide.
-  uint64_t width = (d + 16383) / 16384;
-  if (width < 1024) width = 1024;
-  width = (width + 31) / 32 * 32;
-  const uint32_t ranges = (uint32_t)((d + width - 1) / width);
-  const size_t lds = (size_t)(width / 32) * sizeof(uint32_t);
-  k_aggregate<<<dim3(ranges), dim3(kAggBlock), lds, s>>>(up_idx, up_val, p, N, K_up, delta, d,
-                                                         (uint32_t)width, union_nnz);
+  const uint32_t ranges = aggregate_ranges(d);
+  k_aggregate<<<dim3(ranges), dim3(kAggBlock), 0, s>>>(
+      up_idx, up_val, p, N, K_up, delta, d, union_nnz != nullptr ? range_scratch : nullptr);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || union_nnz == nullptr) return e;
+  k_sum_ranges<<<dim3(1), dim3(1024), 0, s>>>(range_scratch, ranges, union_nnz);
   return hipGetLastError();
 }
 
