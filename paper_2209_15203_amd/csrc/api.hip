@@ -21,6 +21,7 @@ struct bts_ctx {
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
+  uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
   std::vector<void*> owned;     // every device allocation of the context
   // timing of the dominant kernel
   bool profile;
@@ -65,6 +66,14 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
             dev_alloc(ctx, &sc->bucket_off, (size_t)rows * pl.nbk);
   sc->sel = sel;
   return ok;
+}
+
+// The entry/exit tables pay off when most ranges are empty for most workers; they are
+// skipped (binary search instead) when they would be large.
+bool alloc_agg_tables(bts_ctx* ctx) {
+  const size_t words = (size_t)aggregate_ranges(ctx->d) * (size_t)ctx->N;
+  if (ctx->K_up == 0 || words * 8 > (256ull << 20)) return true;
+  return dev_alloc(ctx, &ctx->agg_start, words) && dev_alloc(ctx, &ctx->agg_end, words);
 }
 
 void release(bts_ctx* ctx) {
@@ -151,6 +160,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->agg_ranges = nullptr;
+  ctx->agg_start = ctx->agg_end = nullptr;
   if (hipGetDevice(&ctx->device) != hipSuccess) {
     delete ctx;
     return BTS_EHIP;
@@ -165,6 +175,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
             dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_ranges(d)) &&
+            alloc_agg_tables(ctx) &&
             alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up) &&
             alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn);
   if (!ok) {
@@ -196,7 +207,7 @@ int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, 
   if (!ctx || !p || !delta) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
   hipError_t e = aggregate(ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, delta,
-                           ctx->d, union_nnz, ctx->agg_ranges);
+                           ctx->d, union_nnz, ctx->agg_ranges, ctx->agg_start, ctx->agg_end);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 

@@ -93,10 +93,12 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
 
 // ---- server side ------------------------------------------------------------------------
 // range_scratch: aggregate_ranges(d) words, used only when union_nnz is wanted.
+// tab_start/tab_end: optional aggregate_ranges(d) x N tables (all zero between calls) that
+// replace the per-range binary searches; null = search.
 uint32_t aggregate_ranges(uint64_t d);
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
-                     uint32_t* range_scratch);
+                     uint32_t* range_scratch, uint32_t* tab_start, uint32_t* tab_end);
 hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint32_t K,
                       float alpha_out, float* w, uint64_t d);
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v);

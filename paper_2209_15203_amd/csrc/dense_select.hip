@@ -35,6 +35,9 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
   for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
   __syncthreads();
   const uint32_t prefix = DIGIT == 0 ? 0u : st[row].prefix;
+  // Bin 0 is counted per lane: a sparse row (the server's g_t is mostly exact zeros) would
+  // otherwise serialise the whole wave on one LDS address.
+  uint32_t bin0 = 0;
   for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
        wc += gridDim.x * kWavesPerBlock) {
     const ChunkGeom c = wave_chunk(d, row, wc);
@@ -44,17 +47,26 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
       for (int j = 0; j < 4; ++j) {
         if (mask & (1u << j)) {
           const uint32_t key = key_of(v[j]);
+          uint32_t bin;
+          bool hit;
           if (DIGIT == 0) {
-            atomicAdd(&sh[key >> 20], 1u);
+            bin = key >> 20;
+            hit = true;
           } else if (DIGIT == 1) {
-            if ((key >> 20) == prefix) atomicAdd(&sh[(key >> 10) & 1023u], 1u);
+            bin = (key >> 10) & 1023u;
+            hit = (key >> 20) == prefix;
           } else {
-            if ((key >> 10) == prefix) atomicAdd(&sh[key & 1023u], 1u);
+            bin = key & 1023u;
+            hit = (key >> 10) == prefix;
+          }
+          if (hit) {
+            if (bin == 0) ++bin0; else atomicAdd(&sh[bin], 1u);
           }
         }
       }
     });
   }
+  if (bin0) atomicAdd(&sh[0], bin0);
   __syncthreads();
   uint32_t* h = hist + (uint64_t)row * kBins0;
   for (int i = threadIdx.x; i < NB; i += kBlock) {

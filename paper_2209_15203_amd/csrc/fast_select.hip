@@ -61,6 +61,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
   const uint64_t n_samp = last > first ? (last - first + stride - 1) / stride : 0;
   const uint32_t wave = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  uint32_t bin0 = 0;
   for (uint64_t s0 = (uint64_t)wave * kSliceUnroll; s0 < n_samp;
        s0 += (uint64_t)n_waves * kSliceUnroll) {
     f4 xv[kSliceUnroll], gv[kSliceUnroll];
@@ -85,9 +86,13 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(const float* __restrict_
         v[3] = __fmaf_rn(alpha, gv[u].w, v[3]);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) atomicAdd(&sh[key_of(v[j]) >> kSampleShift], 1u);
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t bin = key_of(v[j]) >> kSampleShift;
+        if (bin == 0) ++bin0; else atomicAdd(&sh[bin], 1u);   // sparse rows: see k_hist
+      }
     }
   }
+  if (bin0) atomicAdd(&sh[0], bin0);
   __syncthreads();
   uint32_t* h = shist + (uint64_t)row * kSampleBins;
   for (int i = threadIdx.x; i < kSampleBins; i += kBlock) {
@@ -487,7 +492,7 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   // dense path, with fewer launches, is the quicker one.
   p.preferred = (uint64_t)rows * d >= (16ull << 20);
   const uint64_t slices = d / 256;
-  uint64_t stride = K / 128;
+  uint64_t stride = K / 64;        // about 128 of the sampled coordinates fall in the top 2K
   if (stride < 16) stride = 16;
   if (stride > 4096) stride = 4096;
   if (stride > slices / 64) stride = slices / 64;

@@ -32,10 +32,27 @@ __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__
   return lo;
 }
 
+// Where each worker's sorted index list enters and leaves each range: pair j of worker q
+// opens range r if its predecessor lies in another range and closes it if its successor
+// does.  The table is all zero between calls (the aggregation clears what it reads).
+__global__ void k_range_bounds(const uint32_t* __restrict__ up_idx, uint32_t N, uint32_t K_up,
+                               uint64_t d, uint32_t* __restrict__ start,
+                               uint32_t* __restrict__ end) {
+  const uint32_t q = blockIdx.y;
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= K_up) return;
+  const uint32_t* row = up_idx + (uint64_t)q * K_up;
+  if (row[j] >= d) return;                       // invalid input never reaches the table
+  const uint32_t r = row[j] / kAggWidth;
+  if (j == 0 || row[j - 1] / kAggWidth != r) start[(uint64_t)r * N + q] = j;
+  if (j + 1 == K_up || row[j + 1] / kAggWidth != r) end[(uint64_t)r * N + q] = j + 1;
+}
+
 __global__ __launch_bounds__(kAggBlock) void k_aggregate(
     const uint32_t* __restrict__ up_idx, const float* __restrict__ up_val,
     const float* __restrict__ p, uint32_t N, uint32_t K_up, float* __restrict__ delta,
-    uint64_t d, uint32_t* __restrict__ range_nnz) {
+    uint64_t d, uint32_t* __restrict__ range_nnz, uint32_t* __restrict__ tab_start,
+    uint32_t* __restrict__ tab_end) {
   __shared__ float acc[kAggWidth];                  // g_t of the touched coordinates
   __shared__ uint32_t touched[kAggWidth / 32];
   __shared__ uint32_t s_lo[kAggTile], s_pref[kAggTile + 1];
@@ -52,9 +69,20 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
     // where each worker of the tile enters and leaves the range
     uint32_t lo = 0, n = 0;
     if (threadIdx.x < nq) {
-      const uint32_t* row = up_idx + (uint64_t)(q0 + threadIdx.x) * K_up;
-      lo = lower_bound_u32(row, K_up, (uint32_t)c0);
-      n = lower_bound_u32(row, K_up, (uint32_t)c1) - lo;   // c1 <= d < 2^32
+      if (tab_start != nullptr) {
+        const uint64_t at = (uint64_t)blockIdx.x * N + q0 + threadIdx.x;
+        lo = tab_start[at];
+        const uint32_t hi = tab_end[at];
+        n = (hi > lo && hi <= K_up) ? hi - lo : 0u;
+        if (hi) {                                            // leave the table clear
+          tab_start[at] = 0;
+          tab_end[at] = 0;
+        }
+      } else {
+        const uint32_t* row = up_idx + (uint64_t)(q0 + threadIdx.x) * K_up;
+        lo = lower_bound_u32(row, K_up, (uint32_t)c0);
+        n = lower_bound_u32(row, K_up, (uint32_t)c1) - lo;   // c1 <= d < 2^32
+      }
       s_p[threadIdx.x] = p[q0 + threadIdx.x];
     }
     uint32_t total;
@@ -148,14 +176,21 @@ uint32_t aggregate_ranges(uint64_t d) { return (uint32_t)((d + kAggWidth - 1) / 
 
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
-                     uint32_t* range_scratch) {
+                     uint32_t* range_scratch, uint32_t* tab_start, uint32_t* tab_end) {
   if (K_up == 0) {
     if (union_nnz != nullptr) return fill_u32(s, union_nnz, 1, 0);
     return hipSuccess;
   }
   const uint32_t ranges = aggregate_ranges(d);
+  if (tab_start != nullptr) {
+    k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(up_idx, N, K_up, d,
+                                                                    tab_start, tab_end);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return e0;
+  }
   k_aggregate<<<dim3(ranges), dim3(kAggBlock), 0, s>>>(
-      up_idx, up_val, p, N, K_up, delta, d, union_nnz != nullptr ? range_scratch : nullptr);
+      up_idx, up_val, p, N, K_up, delta, d, union_nnz != nullptr ? range_scratch : nullptr,
+      tab_start, tab_end);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || union_nnz == nullptr) return e;
   k_sum_ranges<<<dim3(1), dim3(1024), 0, s>>>(range_scratch, ranges, union_nnz);
