@@ -49,6 +49,9 @@ def _load():
     lib.oracle_bidir_step.argtypes = [fp, fp, fp, fp, fp, c.c_int32, c.c_uint64, c.c_uint64,
                                       c.c_uint64, c.c_float, c.c_float, up, fp, up, fp, u64p,
                                       c.c_int32]
+    lib.oracle_unidir_step.argtypes = [fp, fp, fp, fp, c.c_int32, c.c_uint64, c.c_uint64,
+                                       c.c_float, c.c_float, up, fp, up, fp, u64p, c.c_int32]
+    lib.oracle_unidir_step.restype = c.c_int
     for f in (lib.oracle_topk, lib.oracle_worker_stage, lib.oracle_aggregate,
               lib.oracle_downlink, lib.oracle_update, lib.oracle_bidir_step):
         f.restype = c.c_int
@@ -159,3 +162,27 @@ def bidir_step(g: np.ndarray, eps: np.ndarray, delta: np.ndarray, w: np.ndarray,
         raise ValueError(f"oracle_bidir_step failed rc={rc}")
     return {"up_idx": up_idx, "up_val": up_val, "dn_idx": dn_idx, "dn_val": dn_val,
             "union_nnz": int(nnz.value)}
+
+
+def unidir_step(g: np.ndarray, eps: np.ndarray, w: np.ndarray, p: np.ndarray, K_up: int,
+                alpha_in: float, alpha_out: float, nthreads: Optional[int] = None) -> dict:
+    """One iteration of Algorithm 1 (unidirectional Top_K SGD); eps and w updated in place.
+    The server's message g_t is returned sparse (named coordinates, ascending)."""
+    g, eps, w, p = _f32(g, "g"), _f32(eps, "eps"), _f32(w, "w"), _f32(p, "p")
+    N, d = g.shape
+    assert eps.shape == (N, d) and w.shape == (d,) and p.shape == (N,)
+    up_idx = np.empty((N, K_up), dtype=np.uint32)
+    up_val = np.empty((N, K_up), dtype=np.float32)
+    dn_idx = np.empty(N * K_up, dtype=np.uint32)
+    dn_val = np.empty(N * K_up, dtype=np.float32)
+    cnt = ctypes.c_uint64(0)
+    nt = default_threads(N) if nthreads is None else nthreads
+    rc = _load().oracle_unidir_step(_ptr(g), _ptr(eps), _ptr(w), _ptr(p), N, d, K_up, alpha_in,
+                                    alpha_out, _ptr(up_idx), _ptr(up_val), _ptr(dn_idx),
+                                    _ptr(dn_val),
+                                    ctypes.cast(ctypes.byref(cnt), ctypes.c_void_p), nt)
+    if rc:
+        raise ValueError(f"oracle_unidir_step failed rc={rc}")
+    n = int(cnt.value)
+    return {"up_idx": up_idx, "up_val": up_val, "dn_idx": dn_idx[:n].copy(),
+            "dn_val": dn_val[:n].copy(), "dn_count": n}

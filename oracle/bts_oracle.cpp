@@ -22,6 +22,9 @@
 //
 // Build: g++ -O2 -ffp-contract=off -shared -fPIC (no fast-math, no FTZ/DAZ).
 //
+// oracle_unidir_step (Algorithm 1) is pinned by agreeing, on w and eps, with
+// oracle_bidir_step run with K_dn = d (which tests pin to Algorithm 1 independently).
+//
 // Parity pins (see tests/test_oracle_*.py): brute-force subset enumeration on
 // tiny inputs, the three Top_K invariants, the contraction bound of the
 // paper's Eq. "topk_bound", reduction to dense SGD (Eq. 2) when K = d,
@@ -179,6 +182,40 @@ int oracle_bidir_step(const float* g, float* eps, float* delta, float* w, const 
   rc = oracle_downlink(delta, d, K_dn, dn_idx, dn_val);
   if (rc) return rc;
   return oracle_update(dn_idx, dn_val, K_dn, alpha_out, w, d);
+}
+
+// One whole iteration of the loop body of Algorithm 1 (unidirectional Top_K SGD): the
+// worker lines are those of Algorithm 2; the server forms g_t = sum_q p_q Top_K(a^q)
+// (accumulator starts at +0, workers in ascending q, one fused multiply-add each) and
+// sends it uncompressed; the workers apply w = w - alpha_out * g_t.  g_t is non-zero at
+// most at the coordinates some uplink names, so the message is returned sparse: those
+// coordinates in ascending order with their g_t values (dn_idx/dn_val need room for
+// N*K_up pairs; *dn_count receives how many were written).
+int oracle_unidir_step(const float* g, float* eps, float* w, const float* p, int32_t N,
+                       uint64_t d, uint64_t K_up, float alpha_in, float alpha_out,
+                       uint32_t* up_idx, float* up_val, uint32_t* dn_idx, float* dn_val,
+                       uint64_t* dn_count, int32_t nthreads) {
+  int rc = oracle_worker_stage(g, eps, N, d, alpha_in, K_up, up_idx, up_val, nthreads);
+  if (rc) return rc;
+  std::vector<float> gt(d, 0.0f);
+  std::vector<uint8_t> named(d, 0);
+  for (int q = 0; q < N; ++q) {
+    for (uint64_t j = 0; j < K_up; ++j) {
+      const uint32_t i = up_idx[(uint64_t)q * K_up + j];
+      gt[i] = std::fmaf(p[q], up_val[(uint64_t)q * K_up + j], gt[i]);
+      named[i] = 1;
+    }
+  }
+  uint64_t n = 0;
+  for (uint64_t i = 0; i < d; ++i) {
+    if (!named[i]) continue;
+    dn_idx[n] = static_cast<uint32_t>(i);
+    dn_val[n] = gt[i];
+    ++n;
+    w[i] = std::fmaf(-alpha_out, gt[i], w[i]);
+  }
+  *dn_count = n;
+  return 0;
 }
 
 }  // extern "C"

@@ -224,3 +224,31 @@ def test_untouched_coordinates_keep_delta_bits(oracle):
     expect = np.full(d, -0.0, np.float32)
     expect[3], expect[5] = 0.5, -1.0
     assert np.array_equal(bits(delta), bits(expect))
+
+
+def test_algorithm_1_step_equals_bidirectional_with_full_downlink(oracle):
+    """Pin for the unidirectional step: same w and eps as Algorithm 2 with K_dn = d (whose
+    server residual stays zero), message = the named coordinates with the aggregate."""
+    rng = np.random.default_rng(21)
+    N, d, K = 7, 3001, 25
+    p = rng.dirichlet(np.ones(N)).astype(np.float32)
+    w = rng.standard_normal(d).astype(np.float32)
+    w[5], w[6] = 0.0, -0.0
+    eps = np.zeros((N, d), np.float32)
+    w2, eps2, delta2 = w.copy(), eps.copy(), np.zeros(d, np.float32)
+    for t in range(5):
+        g = rng.standard_normal((N, d)).astype(np.float32)
+        uni = oracle.unidir_step(g, eps, w, p, K, 0.07, 0.9)
+        bi = oracle.bidir_step(g, eps2, delta2, w2, p, K, d, 0.07, 0.9)
+        assert np.array_equal(bits(w), bits(w2)) and np.array_equal(bits(eps), bits(eps2))
+        assert not delta2.view(np.uint32).any()
+        assert np.array_equal(uni["up_idx"], bi["up_idx"])
+        assert uni["dn_count"] == bi["union_nnz"] <= N * K
+        named = np.unique(uni["up_idx"])
+        assert np.array_equal(uni["dn_idx"], named.astype(np.uint32))
+        assert np.array_equal(bits(uni["dn_val"]), bits(bi["dn_val"][named]))
+        # the message is the weighted sum of the uplinks (to rounding)
+        ref = np.zeros(d)
+        for q in range(N):
+            np.add.at(ref, uni["up_idx"][q], float(p[q]) * uni["up_val"][q].astype(np.float64))
+        assert np.allclose(uni["dn_val"], ref[named], rtol=0, atol=1e-6)
