@@ -63,6 +63,9 @@ def main() -> int:
                     help="also run one plain copy kernel of known size (2^28 floats read, 2^28 "
                          "written) so that a counter profile of this command can be scaled")
     ap.add_argument("--cpu-rows", type=int, default=0)
+    ap.add_argument("--algo", choices=["bidir", "unidir"], default="bidir",
+                    help="bidir: Algorithm 2 (the headline); unidir: Algorithm 1, the paper's "
+                         "baseline (no downlink compression, no server residual)")
     ap.add_argument("--path", choices=["auto", "dense", "single"], default="auto",
                     help="select path: chosen by shape (default), dense multi-pass only, or "
                          "single-pass wherever the shape allows")
@@ -109,9 +112,18 @@ def main() -> int:
     dn_idx = torch.zeros(cfg.K_dn, dtype=torch.int32, device=dev)
     dn_val = torch.zeros(cfg.K_dn, dtype=torch.float32, device=dev)
 
+    if args.algo == "unidir":
+        msg_idx = torch.zeros(N * cfg.K_up, dtype=torch.int32, device=dev)
+        msg_val = torch.zeros(N * cfg.K_up, dtype=torch.float32, device=dev)
+        msg_cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+
     def step(i):
-        bts.bidir_step(ctx, ring[i % n_buf], eps, delta, w, p, cfg.alpha, 1.0, up_idx, up_val,
-                       dn_idx, dn_val, None)
+        if args.algo == "unidir":
+            bts.unidir_step(ctx, ring[i % n_buf], eps, w, p, cfg.alpha, 1.0, up_idx, up_val,
+                            msg_idx, msg_val, msg_cnt)
+        else:
+            bts.bidir_step(ctx, ring[i % n_buf], eps, delta, w, p, cfg.alpha, 1.0, up_idx,
+                           up_val, dn_idx, dn_val, None)
 
     if args.calibrate_copy:
         src_c = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -134,6 +146,10 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     coords_per_s = N * d / (ms_per_step * 1e-3)
     b_alg = algorithmic_bytes(N, d, cfg.K_up, cfg.K_dn)
+    if args.algo == "unidir":
+        # no downlink select; uplinks written and read, the sparse sum written, w updated at
+        # the (at most N K_up) named coordinates
+        b_alg = 12 * N * d + 16 * N * cfg.K_up + 16 * N * cfg.K_up
     rows_fast, rows_dense = ctx.last_path(0)
 
     # dominant kernel: the dense pass over g and eps (12 algorithmic bytes per coordinate:
@@ -158,7 +174,8 @@ def main() -> int:
             traffic = None
 
     out = {
-        "metric": "gradient coords/sec per bidirectional top-K step (N*d/s)",
+        "metric": "gradient coords/sec per bidirectional top-K step (N*d/s)" if args.algo == "bidir"
+        else "gradient coords/sec per unidirectional top-K step (N*d/s)",
         "value": coords_per_s,
         "unit": "coords/s",
         "n_gpus": 1,

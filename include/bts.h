@@ -116,6 +116,23 @@ int bidir_step(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
                uint32_t* dn_idx, float* dn_val, uint32_t* union_nnz);
 
 /*
+ * One whole iteration of the loop body of Algorithm 1 (unidirectional Top_K SGD, the
+ * paper's baseline): the worker lines are those of Algorithm 2 (topk_compress); the server
+ * forms g_t = sum_q p_q Top_K(a^q) (accumulator starts at +0, workers in ascending q, one
+ * fused multiply-add each) and sends it uncompressed; the workers apply
+ * w -= alpha_out * g_t.  There is no server residual.  g_t is non-zero at most at the
+ * coordinates some uplink names (at most K_uplink N of them, communication section), so
+ * the message is produced sparse:
+ * dn_idx, dn_val  nullable (both or neither); room for N * K_up pairs; receive the named
+ *                 coordinates in ascending order and their g_t values.
+ * dn_count        nullable; one uint32 on the device: the number of pairs.
+ * Same results as bidir_step with K_dn = d and a zero delta.
+ */
+int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float* p,
+                float alpha_in, float alpha_out, uint32_t* up_idx, float* up_val,
+                uint32_t* dn_idx, float* dn_val, uint32_t* dn_count);
+
+/*
  * Timing of the dominant kernel (the dense pass over g and eps in topk_compress).  While
  * enabled, the library brackets that kernel with HIP events on the context's stream.
  * bts_profile_read synchronises those events and returns the summed kernel time in

@@ -7,7 +7,7 @@ no CPU fallback: importing :mod:`paper_2209_15203_amd.binding` without the built
 fails loudly.
 """
 from .binding import (BtsContext, BtsError, bidir_step, downlink_topk, lib_path, load_library,
-                      sparse_aggregate, sparse_sgd_update, topk_compress)
+                      sparse_aggregate, sparse_sgd_update, topk_compress, unidir_step)
 
 __all__ = ["BtsContext", "BtsError", "bidir_step", "downlink_topk", "lib_path", "load_library",
-           "sparse_aggregate", "sparse_sgd_update", "topk_compress"]
+           "sparse_aggregate", "sparse_sgd_update", "topk_compress", "unidir_step"]

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libbts.so")
 
 EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
            "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
-           "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path"]
+           "unidir_step", "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path"]
 
 _lib = None
 
@@ -45,6 +45,7 @@ def load_library():
     lib.downlink_topk.argtypes = [vp, vp, vp, vp]
     lib.sparse_sgd_update.argtypes = [vp, vp, vp, u32, f32, vp]
     lib.bidir_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
+    lib.unidir_step.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
     lib.bts_profile_enable.argtypes = [vp, C.c_int]
     lib.bts_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64)]
     lib.bts_last_path.argtypes = [vp, C.c_int, C.POINTER(u32), C.POINTER(u32)]
@@ -157,3 +158,12 @@ def bidir_step(ctx: BtsContext, g, eps, delta, w, p, alpha_in: float, alpha_out:
                                   _ptr(up_val, F32, "up_val"), _ptr(dn_idx, U32, "dn_idx"),
                                   _ptr(dn_val, F32, "dn_val"),
                                   _ptr(union_nnz, U32, "union_nnz")), "bidir_step")
+
+
+def unidir_step(ctx: BtsContext, g, eps, w, p, alpha_in: float, alpha_out: float, up_idx, up_val,
+                dn_idx=None, dn_val=None, dn_count=None) -> None:
+    ctx.check(ctx._lib.unidir_step(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"),
+                                   _ptr(w, F32, "w"), _ptr(p, F32, "p"), alpha_in, alpha_out,
+                                   _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val"),
+                                   _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val"),
+                                   _ptr(dn_count, U32, "dn_count")), "unidir_step")

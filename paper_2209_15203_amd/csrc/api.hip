@@ -21,6 +21,7 @@ struct bts_ctx {
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
+  uint32_t* agg_offsets;        // their exclusive scan (unidirectional message placement)
   uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
   std::vector<void*> owned;     // every device allocation of the context
   // timing of the dominant kernel
@@ -160,6 +161,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->agg_ranges = nullptr;
+  ctx->agg_offsets = nullptr;
   ctx->agg_start = ctx->agg_end = nullptr;
   if (hipGetDevice(&ctx->device) != hipSuccess) {
     delete ctx;
@@ -175,6 +177,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
             dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_ranges(d)) &&
+            dev_alloc(ctx, &ctx->agg_offsets, (size_t)aggregate_ranges(d)) &&
             alloc_agg_tables(ctx) &&
             alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up) &&
             alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn);
@@ -240,6 +243,21 @@ int bidir_step(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
   rc = downlink_topk(ctx, delta, dn_idx, dn_val);
   if (rc != BTS_OK) return rc;
   return sparse_sgd_update(ctx, dn_idx, dn_val, ctx->K_dn, alpha_out, w);
+}
+
+int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float* p,
+                float alpha_in, float alpha_out, uint32_t* up_idx, float* up_val,
+                uint32_t* dn_idx, float* dn_val, uint32_t* dn_count) {
+  if (!ctx || !g || !eps || !w || !p) return BTS_EINVAL;
+  if (!aligned16(g) || !aligned16(eps)) return BTS_EINVAL;
+  if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
+  if ((dn_idx == nullptr) != (dn_val == nullptr)) return BTS_EINVAL;
+  int rc = topk_compress(ctx, g, eps, alpha_in, up_idx, up_val);
+  if (rc != BTS_OK) return rc;
+  hipError_t e = aggregate_update_unidirectional(
+      ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, w, ctx->d, alpha_out, dn_idx,
+      dn_val, dn_count, ctx->agg_ranges, ctx->agg_offsets, ctx->agg_start, ctx->agg_end);
+  return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
 int bts_profile_enable(bts_ctx* ctx, int on) {

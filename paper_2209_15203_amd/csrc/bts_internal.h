@@ -99,6 +99,16 @@ uint32_t aggregate_ranges(uint64_t d);
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
                      uint32_t* range_scratch, uint32_t* tab_start, uint32_t* tab_end);
+// Algorithm 1's server and update in one: w -= alpha_out * sum_q p_q Top_K(a^q), the sum
+// also returned as a sparse message (named coordinates ascending; msg_idx/msg_val nullable,
+// room for N*K_up pairs; msg_count nullable).  range_cnt/range_off: aggregate_ranges(d)
+// words each.
+hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx,
+                                           const float* up_val, const float* p, uint32_t N,
+                                           uint32_t K_up, float* w, uint64_t d, float alpha_out,
+                                           uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
+                                           uint32_t* range_cnt, uint32_t* range_off,
+                                           uint32_t* tab_start, uint32_t* tab_end);
 hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint32_t K,
                       float alpha_out, float* w, uint64_t d);
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v);

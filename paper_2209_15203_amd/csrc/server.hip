@@ -48,11 +48,18 @@ __global__ void k_range_bounds(const uint32_t* __restrict__ up_idx, uint32_t N, 
   if (j + 1 == K_up || row[j + 1] / kAggWidth != r) end[(uint64_t)r * N + q] = j + 1;
 }
 
+// MODE 0: bidirectional server (Algorithm 2): delta[i] = delta[i] + sum_q p_q v_q[i].
+// MODE 1: count the distinct coordinates named in each range and nothing else.
+// MODE 2: unidirectional server and update (Algorithm 1): g_t[i] = sum_q p_q v_q[i] from +0,
+//         the named coordinates and their g_t written in ascending order to the message at
+//         range_off[range] + rank, and w[i] = fma(-alpha_out, g_t[i], w[i]).
+template <int MODE>
 __global__ __launch_bounds__(kAggBlock) void k_aggregate(
     const uint32_t* __restrict__ up_idx, const float* __restrict__ up_val,
-    const float* __restrict__ p, uint32_t N, uint32_t K_up, float* __restrict__ delta,
+    const float* __restrict__ p, uint32_t N, uint32_t K_up, float* __restrict__ dense,
     uint64_t d, uint32_t* __restrict__ range_nnz, uint32_t* __restrict__ tab_start,
-    uint32_t* __restrict__ tab_end) {
+    uint32_t* __restrict__ tab_end, const uint32_t* __restrict__ range_off, float neg_alpha,
+    uint32_t* __restrict__ msg_idx, float* __restrict__ msg_val) {
   __shared__ float acc[kAggWidth];                  // g_t of the touched coordinates
   __shared__ uint32_t touched[kAggWidth / 32];
   __shared__ uint32_t s_lo[kAggTile], s_pref[kAggTile + 1];
@@ -74,7 +81,7 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
         lo = tab_start[at];
         const uint32_t hi = tab_end[at];
         n = (hi > lo && hi <= K_up) ? hi - lo : 0u;
-        if (hi) {                                            // leave the table clear
+        if (MODE != 1 && hi) {                               // leave the table clear
           tab_start[at] = 0;
           tab_end[at] = 0;
         }
@@ -109,45 +116,91 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
           rel = i - (uint32_t)c0;
           const uint32_t bit = 1u << (rel & 31);
           const uint32_t old = atomicOr(&touched[rel >> 5], bit);
-          if (!(old & bit)) {                                // first touch: fetch delta
-            acc[rel] = delta[i];
+          if (!(old & bit)) {                                // first touch: start value
+            if (MODE == 0) acc[rel] = dense[i];
+            if (MODE == 2) acc[rel] = 0.0f;
             ++fresh;
           }
         }
-        e_rel[e - e0] = rel;
-        e_val[e - e0] = up_val[src];
+        if (MODE != 1) {
+          e_rel[e - e0] = rel;
+          e_val[e - e0] = up_val[src];
+        }
       }
       __syncthreads();
-      // one round per worker present in the stage, in ascending q
-      while (t_first + 1 < nq && s_pref[t_first + 1] <= e0) ++t_first;
-      for (uint32_t t = t_first; t < nq && s_pref[t] < e1; ++t) {
-        const uint32_t a = max(s_pref[t], e0), b = min(s_pref[t + 1], e1);
-        if (b <= a) continue;                                // uniform over the block
-        const float pq = s_p[t];
-        for (uint32_t e = a + threadIdx.x; e < b; e += kAggBlock) {
-          const uint32_t rel = e_rel[e - e0];
-          if (rel != 0xFFFFFFFFu) acc[rel] = __fmaf_rn(pq, e_val[e - e0], acc[rel]);
+      if (MODE != 1) {
+        // one round per worker present in the stage, in ascending q
+        while (t_first + 1 < nq && s_pref[t_first + 1] <= e0) ++t_first;
+        for (uint32_t t = t_first; t < nq && s_pref[t] < e1; ++t) {
+          const uint32_t a = max(s_pref[t], e0), b = min(s_pref[t + 1], e1);
+          if (b <= a) continue;                              // uniform over the block
+          const float pq = s_p[t];
+          for (uint32_t e = a + threadIdx.x; e < b; e += kAggBlock) {
+            const uint32_t rel = e_rel[e - e0];
+            if (rel != 0xFFFFFFFFu) acc[rel] = __fmaf_rn(pq, e_val[e - e0], acc[rel]);
+          }
+          __syncthreads();                                   // next worker may name the same i
         }
-        __syncthreads();                                     // next worker may name the same i
       }
     }
     __syncthreads();
   }
-  // write the touched coordinates back
-  for (uint32_t w = threadIdx.x; w < kAggWidth / 32; w += kAggBlock) {
-    uint32_t bits = touched[w];
+  if (MODE == 0) {
+    // write the touched coordinates back
+    for (uint32_t w = threadIdx.x; w < kAggWidth / 32; w += kAggBlock) {
+      uint32_t bits = touched[w];
+      while (bits) {
+        const uint32_t t = __ffs(bits) - 1;
+        bits &= bits - 1;
+        const uint32_t rel = w * 32 + t;
+        dense[c0 + rel] = acc[rel];
+      }
+    }
+  }
+  if (MODE == 2) {
+    // ordered message: rank of a coordinate = set bits below it in the range's bitmap
+    static_assert(kAggWidth / 32 <= kAggBlock, "one bitmap word per thread");
+    const uint32_t word = threadIdx.x < kAggWidth / 32 ? touched[threadIdx.x] : 0u;
+    uint32_t total;
+    uint32_t pos = range_off[blockIdx.x] + block_exclusive_scan(__popc(word), lds, &total);
+    uint32_t bits = word;
     while (bits) {
       const uint32_t t = __ffs(bits) - 1;
       bits &= bits - 1;
-      const uint32_t rel = w * 32 + t;
-      delta[c0 + rel] = acc[rel];
+      const uint32_t rel = threadIdx.x * 32 + t;
+      const float gt = acc[rel];
+      if (msg_idx != nullptr) {
+        msg_idx[pos] = (uint32_t)c0 + rel;
+        msg_val[pos] = gt;
+      }
+      dense[c0 + rel] = __fmaf_rn(neg_alpha, gt, dense[c0 + rel]);
+      ++pos;
     }
   }
-  if (range_nnz != nullptr) {
+  if ((MODE == 0 || MODE == 1) && range_nnz != nullptr) {
     uint32_t total;
     (void)block_exclusive_scan(fresh, lds, &total);
     if (threadIdx.x == 0) range_nnz[blockIdx.x] = total;
   }
+}
+
+// Exclusive scan of the per-range counts (one block); *total_out receives the sum.
+__global__ __launch_bounds__(1024) void k_scan_ranges(const uint32_t* __restrict__ cnt,
+                                                      uint32_t* __restrict__ off, uint32_t n,
+                                                      uint32_t* __restrict__ total_out) {
+  __shared__ uint32_t lds[1024 / kWave + 1];
+  const uint32_t per = (n + blockDim.x - 1) / blockDim.x;
+  const uint32_t b = min(threadIdx.x * per, n), e = min(b + per, n);
+  uint32_t s = 0;
+  for (uint32_t i = b; i < e; ++i) s += cnt[i];
+  uint32_t total;
+  uint32_t run = block_exclusive_scan(s, lds, &total);
+  for (uint32_t i = b; i < e; ++i) {
+    const uint32_t t = cnt[i];
+    off[i] = run;
+    run += t;
+  }
+  if (threadIdx.x == 0 && total_out != nullptr) *total_out = total;
 }
 
 // Sum of the per-range counts of distinct coordinates: one block.
@@ -188,12 +241,43 @@ hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val,
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
   }
-  k_aggregate<<<dim3(ranges), dim3(kAggBlock), 0, s>>>(
+  k_aggregate<0><<<dim3(ranges), dim3(kAggBlock), 0, s>>>(
       up_idx, up_val, p, N, K_up, delta, d, union_nnz != nullptr ? range_scratch : nullptr,
-      tab_start, tab_end);
+      tab_start, tab_end, nullptr, 0.0f, nullptr, nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || union_nnz == nullptr) return e;
   k_sum_ranges<<<dim3(1), dim3(1024), 0, s>>>(range_scratch, ranges, union_nnz);
+  return hipGetLastError();
+}
+
+hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx,
+                                           const float* up_val, const float* p, uint32_t N,
+                                           uint32_t K_up, float* w, uint64_t d, float alpha_out,
+                                           uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
+                                           uint32_t* range_cnt, uint32_t* range_off,
+                                           uint32_t* tab_start, uint32_t* tab_end) {
+  if (K_up == 0) {
+    if (msg_count != nullptr) return fill_u32(s, msg_count, 1, 0);
+    return hipSuccess;
+  }
+  const uint32_t ranges = aggregate_ranges(d);
+  if (tab_start != nullptr) {
+    k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(up_idx, N, K_up, d,
+                                                                    tab_start, tab_end);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return e0;
+  }
+  k_aggregate<1><<<dim3(ranges), dim3(kAggBlock), 0, s>>>(up_idx, up_val, p, N, K_up, nullptr, d,
+                                                          range_cnt, tab_start, tab_end, nullptr,
+                                                          0.0f, nullptr, nullptr);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_scan_ranges<<<dim3(1), dim3(1024), 0, s>>>(range_cnt, range_off, ranges, msg_count);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_aggregate<2><<<dim3(ranges), dim3(kAggBlock), 0, s>>>(up_idx, up_val, p, N, K_up, w, d,
+                                                          nullptr, tab_start, tab_end, range_off,
+                                                          -alpha_out, msg_idx, msg_val);
   return hipGetLastError();
 }
 

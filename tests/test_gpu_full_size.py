@@ -120,3 +120,43 @@ def test_full_size_config(oracle, name):
             wt_after = corrected_sequence(w, eps, delta, p_host)
             err = (wt_after - (wt_before - float(np.float32(cfg.alpha)) * step_dir)).abs().max()
             assert float(err) < 2e-6, f"{tag}: Lemma 1 identity off by {float(err)}"
+
+
+@pytest.mark.timeout(600)
+def test_full_size_unidirectional_c3(oracle):
+    """Algorithm 1 at a benchmark size (C3: 32 workers, d = 25,557,032): two steps, every
+    output bit for bit against the oracle."""
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS["C3"]
+    N, d, K = cfg.N, cfg.d, cfg.K_up
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p_host = wl.p_weights(cfg)
+    w0 = wl.weights0(cfg, D)
+    ctx = bts.BtsContext(N, d, K, cfg.K_dn)
+    eps = torch.zeros((N, d), dtype=torch.float32, device=D)
+    w = w0.clone()
+    p = torch.from_numpy(p_host).to(D)
+    ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+    di = torch.zeros(N * K, dtype=torch.int32, device=D)
+    dv = torch.zeros(N * K, dtype=torch.float32, device=D)
+    dc = torch.zeros(1, dtype=torch.int32, device=D)
+    g = torch.empty((N, d), dtype=torch.float32, device=D)
+    h_eps = np.zeros((N, d), np.float32)
+    h_w = w0.cpu().numpy().copy()
+    for t in (1, 2):
+        src.fill(t, g)
+        print(f"[C3 unidirectional] step {t}/2", flush=True)
+        bts.unidir_step(ctx, g, eps, w, p, cfg.alpha, 1.0, ui, uv, di, dv, dc)
+        torch.cuda.synchronize()
+        want = oracle.unidir_step(g.cpu().numpy(), h_eps, h_w, p_host, K, cfg.alpha, 1.0)
+        n = int(dc.item())
+        assert n == want["dn_count"]
+        G.assert_same_bits(ui, want["up_idx"], f"step {t} up_idx")
+        G.assert_same_bits(uv, want["up_val"], f"step {t} up_val")
+        G.assert_same_bits(eps, h_eps, f"step {t} eps")
+        G.assert_same_bits(di[:n], want["dn_idx"], f"step {t} message indices")
+        G.assert_same_bits(dv[:n], want["dn_val"], f"step {t} message values")
+        G.assert_same_bits(w, h_w, f"step {t} w")

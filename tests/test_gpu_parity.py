@@ -261,6 +261,54 @@ def test_bidir_step_scaled_configs(G, oracle, name, mode, path):
             assert st.ctx.last_path(0)[0] > 0, "no uplink row took the single-pass path"
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS])
+def test_unidir_step_scaled_configs(G, oracle, name, path):
+    """Algorithm 1 (the paper's unidirectional baseline) as its own entry point: worker
+    compression, then w -= alpha_out * sum_q p_q Top_K(a^q) with the sum returned as a
+    sparse message; every output bit for bit against the oracle over three steps."""
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS[name].scaled(SMALL[name], N=min(wl.CONFIGS[name].N, 16), steps=3)
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p = wl.p_weights(wl.CONFIGS[name])[:cfg.N].copy()
+    N, d, K = cfg.N, cfg.d, cfg.K_up
+    ctx = bts.BtsContext(N, d, K, K)
+    ctx.set_path(path)
+    eps = torch.zeros((N, d), device=D)
+    w0 = wl.weights0(cfg, "cpu").numpy()
+    w = torch.from_numpy(w0.copy()).to(D)
+    tp = torch.from_numpy(p).to(D)
+    ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), device=D)
+    di = torch.full((N * K,), -1, dtype=torch.int32, device=D)
+    dv = torch.zeros(N * K, device=D)
+    dc = torch.zeros(1, dtype=torch.int32, device=D)
+    h_eps, h_w = np.zeros((N, d), np.float32), w0.copy()
+    for t in range(1, 4):
+        g = src.step(t)
+        a_out = 1.0 if t < 3 else 0.5
+        bts.unidir_step(ctx, g, eps, w, tp, cfg.alpha, a_out, ui, uv, di, dv, dc)
+        torch.cuda.synchronize()
+        want = oracle.unidir_step(g.cpu().numpy(), h_eps, h_w, p, K, cfg.alpha, a_out)
+        n = int(dc.item())
+        assert n == want["dn_count"]
+        G.assert_same_bits(ui, want["up_idx"], f"step {t} up_idx")
+        G.assert_same_bits(uv, want["up_val"], f"step {t} up_val")
+        G.assert_same_bits(eps, h_eps, f"step {t} eps")
+        G.assert_same_bits(di[:n], want["dn_idx"], f"step {t} message indices")
+        G.assert_same_bits(dv[:n], want["dn_val"], f"step {t} message values")
+        G.assert_same_bits(w, h_w, f"step {t} w")
+    # the message is optional
+    w2 = w.clone()
+    g = src.step(4)
+    e2 = eps.clone()
+    bts.unidir_step(ctx, g, eps, w, tp, cfg.alpha, 1.0, ui, uv, di, dv, dc)
+    bts.unidir_step(ctx, g, e2, w2, tp, cfg.alpha, 1.0, ui, uv, None, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(w.view(torch.int32), w2.view(torch.int32))
+
+
 def test_bidir_step_equals_the_four_calls_and_is_deterministic(G):
     import paper_2209_15203_amd as bts
     cfg = wl.CONFIGS["C4"].scaled(80_005, N=8, steps=2)
