@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="C5")
+    ap.add_argument("--shape", default="",
+                    help="custom workload instead of --config: N,d,num/den (K = that fraction of "
+                         "d both ways, N(0,1) gradients, p = 1/N), e.g. 20,20040522,1/1000")
     ap.add_argument("--buffers", type=int, default=0,
                     help="distinct gradient batches kept in HBM (0 = as many as steps+warmup, "
                          "capped by memory)")
@@ -86,7 +89,14 @@ def main() -> int:
     bts.load_library()                      # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    cfg = wl.CONFIGS[args.config]
+    if args.shape:
+        n_s, d_s, frac = args.shape.split(",")
+        num, den = (int(v) for v in frac.split("/"))
+        k_s = wl.k_from_fraction(int(d_s), num, den)
+        cfg = wl.Config(f"shape-N{n_s}-d{d_s}", 200, int(n_s), int(d_s), k_s, k_s, args.steps,
+                        "normal")
+    else:
+        cfg = wl.CONFIGS[args.config]
     N, d = cfg.N, cfg.d
 
     total = torch.cuda.get_device_properties(dev).total_memory

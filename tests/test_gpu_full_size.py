@@ -160,3 +160,59 @@ def test_full_size_unidirectional_c3(oracle):
         G.assert_same_bits(di[:n], want["dn_idx"], f"step {t} message indices")
         G.assert_same_bits(dv[:n], want["dn_val"], f"step {t} message values")
         G.assert_same_bits(w, h_w, f"step {t} w")
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("path", [1, 2])
+def test_indices_beyond_2_to_31(path):
+    """One row longer than 2^31 coordinates (d = 2^31 + 2^20 + 3, ragged tail): indices use
+    the full unsigned 32-bit range.  The oracle would need many minutes to sort such a row,
+    so the expected result is built in: bounded noise (|x| <= 1) with 3K planted values of
+    distinct larger magnitudes, some of them past 2^31 and in the last partial chunk.  Top_K
+    must return exactly the K largest planted coordinates, ascending, and zero them."""
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    D = G.dev()
+    d = (1 << 31) + (1 << 20) + 3
+    K, P = 4096, 3 * 4096
+    g = torch.empty(d, dtype=torch.float32, device=D)
+    step = 1 << 26
+    gen = torch.Generator(device=D)
+    gen.manual_seed(77)
+    for s in range(0, d, step):
+        n = min(step, d - s)
+        g[s:s + n] = torch.rand(n, generator=gen, device=D) * 2.0 - 1.0
+    rng = np.random.default_rng(5)
+    planted = np.unique(np.concatenate([
+        rng.integers(0, d, size=2 * P, dtype=np.int64),
+        np.arange(d - 40, d, dtype=np.int64),                   # the ragged tail
+        (1 << 31) + np.arange(-12, 12, dtype=np.int64)]))       # around the sign bit of int32
+    must = np.concatenate([np.arange(d - 40, d), (1 << 31) + np.arange(-12, 12)])
+    rest = np.setdiff1d(planted, must)
+    planted = np.concatenate([must, rng.permutation(rest)[:P - must.size]])
+    # distinct magnitudes 2 + j/P; the special positions get the largest ones
+    mags = (2.0 + (P - 1 - np.arange(P, dtype=np.float32)) / P).astype(np.float32)
+    vals = mags * rng.choice(np.array([-1.0, 1.0], np.float32), size=P)
+    g[torch.from_numpy(planted).to(D)] = torch.from_numpy(vals).to(D)
+    order = np.argsort(planted[:K])
+    want_idx, want_val = planted[:K][order], vals[:K][order]    # the K largest magnitudes
+    assert want_idx[-1] == d - 1 and (want_idx > (1 << 31)).sum() >= 12
+    eps = torch.zeros(d, dtype=torch.float32, device=D)
+    ctx = bts.BtsContext(1, d, K, K)
+    ctx.set_path(path)
+    ui = torch.zeros((1, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((1, K), dtype=torch.float32, device=D)
+    bts.topk_compress(ctx, g.view(1, d), eps.view(1, d), 1.0, ui, uv)
+    torch.cuda.synchronize()
+    got_idx = ui.cpu().numpy().view(np.uint32).ravel().astype(np.int64)
+    assert np.array_equal(got_idx, want_idx)
+    G.assert_same_bits(uv.ravel(), want_val, "values")
+    t_sel = torch.from_numpy(want_idx).to(D)
+    assert not bool(eps[t_sel].view(torch.int32).any())
+    # everything else is a = 0 + 1*g = g, untouched
+    probe = torch.cat([torch.from_numpy(rng.integers(0, d, size=1 << 20, dtype=np.int64)),
+                       torch.from_numpy(planted[K:])]).to(D)
+    keep = ~torch.isin(probe, t_sel)
+    assert torch.equal(eps[probe][keep].view(torch.int32), g[probe][keep].view(torch.int32))
+    fast, dense = ctx.last_path(0)
+    assert (fast, dense) == ((1, 0) if path == 2 else (0, 1))
