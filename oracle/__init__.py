@@ -52,6 +52,10 @@ def _load():
     lib.oracle_unidir_step.argtypes = [fp, fp, fp, fp, c.c_int32, c.c_uint64, c.c_uint64,
                                        c.c_float, c.c_float, up, fp, up, fp, u64p, c.c_int32]
     lib.oracle_unidir_step.restype = c.c_int
+    lib.oracle_bidir_step_diag.argtypes = [fp, fp, fp, fp, fp, c.c_int32, c.c_uint64, c.c_uint64,
+                                           c.c_uint64, c.c_float, c.c_float, up, fp, up, fp,
+                                           c.c_void_p, c.c_int32]
+    lib.oracle_bidir_step_diag.restype = c.c_int
     for f in (lib.oracle_topk, lib.oracle_worker_stage, lib.oracle_aggregate,
               lib.oracle_downlink, lib.oracle_update, lib.oracle_bidir_step):
         f.restype = c.c_int
@@ -186,3 +190,32 @@ def unidir_step(g: np.ndarray, eps: np.ndarray, w: np.ndarray, p: np.ndarray, K_
     n = int(cnt.value)
     return {"up_idx": up_idx, "up_val": up_val, "dn_idx": dn_idx[:n].copy(),
             "dn_val": dn_val[:n].copy(), "dn_count": n}
+
+
+DIAG_FIELDS = ("rho", "rho_hat", "one_minus_gamma_max", "denominator", "rho_numerator",
+               "rho_hat_numerator", "nnz_fraction", "one_minus_gamma_server")
+
+
+def bidir_step_diag(g: np.ndarray, eps: np.ndarray, delta: np.ndarray, w: np.ndarray,
+                    p: np.ndarray, K_up: int, K_dn: int, alpha_in: float, alpha_out: float,
+                    nthreads: Optional[int] = None) -> dict:
+    """One iteration of Algorithm 2 plus the per-step estimates of rho, rho_hat and 1-gamma
+    (the constants of Assumptions 2, 5 and 6 the paper measures)."""
+    g, eps, delta, w, p = (_f32(g, "g"), _f32(eps, "eps"), _f32(delta, "delta"), _f32(w, "w"),
+                           _f32(p, "p"))
+    N, d = g.shape
+    up_idx = np.empty((N, K_up), dtype=np.uint32)
+    up_val = np.empty((N, K_up), dtype=np.float32)
+    dn_idx = np.empty(K_dn, dtype=np.uint32)
+    dn_val = np.empty(K_dn, dtype=np.float32)
+    diag = np.zeros(8 + N, dtype=np.float64)
+    nt = default_threads(N) if nthreads is None else nthreads
+    rc = _load().oracle_bidir_step_diag(_ptr(g), _ptr(eps), _ptr(delta), _ptr(w), _ptr(p), N, d,
+                                        K_up, K_dn, alpha_in, alpha_out, _ptr(up_idx),
+                                        _ptr(up_val), _ptr(dn_idx), _ptr(dn_val), _ptr(diag), nt)
+    if rc:
+        raise ValueError(f"oracle_bidir_step_diag failed rc={rc}")
+    out = {"up_idx": up_idx, "up_val": up_val, "dn_idx": dn_idx, "dn_val": dn_val, "diag": diag}
+    out.update({k: float(diag[i]) for i, k in enumerate(DIAG_FIELDS)})
+    out["one_minus_gamma_workers"] = diag[8:].copy()
+    return out

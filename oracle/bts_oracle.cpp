@@ -218,4 +218,93 @@ int oracle_unidir_step(const float* g, float* eps, float* w, const float* p, int
   return 0;
 }
 
+// One iteration of Algorithm 2 together with the per-step estimates of the constants the
+// paper measures in its section on convergence-bound constants:
+//   rho      = |Top_K(delta_{t-1} + sum_q p_q a^q) - Top_K(delta_{t-1} + sum_q Top_K(p_q a^q))|_2
+//              / |alpha_{t-1} sum_q p_q g^q|_2                       (left/right side of Assumption 5)
+//   rho_hat  = |Top_K(sum_q p_q a^q) - sum_q Top_K(p_q a^q)|_2 / |alpha_{t-1} sum_q p_q g^q|_2
+//                                                                    (Assumption 6, unidirectional)
+//   1-gamma  = |Top_K(x) - x|_2^2 / |x|_2^2 for every compression of the step (x = a^q, x = g_t)
+//   nnz      = distinct coordinates named by the uplinks / d          (communication section)
+// The dense sums are fp32 fused multiply-add chains in ascending q (from +0, or from
+// delta_{t-1}), Top_K(p_q a^q) is read as p_q Top_K(a^q) as in Algorithm 2, the second
+// Top_K in rho is the step's own downlink message, the first uses K_dn and the one in
+// rho_hat K_up.  Norms accumulate in fp64.
+// diag: 8 + N doubles: rho, rho_hat, max(1-gamma), |alpha sum p g|, numerator of rho,
+// numerator of rho_hat, nnz fraction, 1-gamma of the server, then 1-gamma of each worker.
+int oracle_bidir_step_diag(const float* g, float* eps, float* delta, float* w, const float* p,
+                           int32_t N, uint64_t d, uint64_t K_up, uint64_t K_dn, float alpha_in,
+                           float alpha_out, uint32_t* up_idx, float* up_val, uint32_t* dn_idx,
+                           float* dn_val, double* diag, int32_t nthreads) {
+  if (N <= 0 || K_up > d || K_dn > d || K_up == 0 || K_dn == 0) return -1;
+  std::vector<float> s(d, 0.0f), u(d, 0.0f), v(delta, delta + d);
+  for (int q = 0; q < N; ++q) {
+    const float* gq = g + (uint64_t)q * d;
+    const float* eq = eps + (uint64_t)q * d;
+    for (uint64_t i = 0; i < d; ++i) {
+      const float a = std::fmaf(alpha_in, gq[i], eq[i]);
+      s[i] = std::fmaf(p[q], gq[i], s[i]);
+      u[i] = std::fmaf(p[q], a, u[i]);
+      v[i] = std::fmaf(p[q], a, v[i]);
+    }
+  }
+  uint64_t nnz = 0;
+  int rc = oracle_bidir_step(g, eps, delta, w, p, N, d, K_up, K_dn, alpha_in, alpha_out, up_idx,
+                             up_val, dn_idx, dn_val, &nnz, nthreads);
+  if (rc) return rc;
+  auto sq = [](double x) { return x * x; };
+  // denominator
+  double den = 0.0;
+  for (uint64_t i = 0; i < d; ++i) den += sq((double)alpha_in * (double)s[i]);
+  den = std::sqrt(den);
+  // rho: Top_K(v) against the step's downlink message
+  std::vector<uint32_t> ti(std::max(K_up, K_dn));
+  std::vector<float> tv(std::max(K_up, K_dn));
+  std::vector<double> dense(d, 0.0);
+  topk_plain(v.data(), d, K_dn, ti.data(), tv.data(), nullptr);
+  for (uint64_t j = 0; j < K_dn; ++j) dense[ti[j]] += tv[j];
+  for (uint64_t j = 0; j < K_dn; ++j) dense[dn_idx[j]] -= dn_val[j];
+  double num_rho = 0.0;
+  for (uint64_t i = 0; i < d; ++i) num_rho += sq(dense[i]);
+  num_rho = std::sqrt(num_rho);
+  // rho_hat: Top_K(u) against sum_q p_q Top_K(a^q)
+  std::vector<float> m(d, 0.0f);
+  for (int q = 0; q < N; ++q)
+    for (uint64_t j = 0; j < K_up; ++j) {
+      const uint64_t at = (uint64_t)q * K_up + j;
+      m[up_idx[at]] = std::fmaf(p[q], up_val[at], m[up_idx[at]]);
+    }
+  std::fill(dense.begin(), dense.end(), 0.0);
+  topk_plain(u.data(), d, K_up, ti.data(), tv.data(), nullptr);
+  for (uint64_t j = 0; j < K_up; ++j) dense[ti[j]] += tv[j];
+  double num_hat = 0.0;
+  for (uint64_t i = 0; i < d; ++i) num_hat += sq(dense[i] - (double)m[i]);
+  num_hat = std::sqrt(num_hat);
+  // 1 - gamma of every compression: residual energy over input energy
+  double worst = 0.0;
+  for (int q = 0; q < N; ++q) {
+    double res = 0.0, sent = 0.0;
+    for (uint64_t i = 0; i < d; ++i) res += sq(eps[(uint64_t)q * d + i]);
+    for (uint64_t j = 0; j < K_up; ++j) sent += sq(up_val[(uint64_t)q * K_up + j]);
+    const double r = res + sent > 0.0 ? res / (res + sent) : 0.0;
+    diag[8 + q] = r;
+    worst = std::max(worst, r);
+  }
+  {
+    double res = 0.0, sent = 0.0;
+    for (uint64_t i = 0; i < d; ++i) res += sq(delta[i]);
+    for (uint64_t j = 0; j < K_dn; ++j) sent += sq(dn_val[j]);
+    diag[7] = res + sent > 0.0 ? res / (res + sent) : 0.0;
+    worst = std::max(worst, diag[7]);
+  }
+  diag[0] = den > 0.0 ? num_rho / den : 0.0;
+  diag[1] = den > 0.0 ? num_hat / den : 0.0;
+  diag[2] = worst;
+  diag[3] = den;
+  diag[4] = num_rho;
+  diag[5] = num_hat;
+  diag[6] = (double)nnz / (double)d;
+  return 0;
+}
+
 }  // extern "C"
