@@ -66,9 +66,10 @@ def main() -> int:
                     help="also run one plain copy kernel of known size (2^28 floats read, 2^28 "
                          "written) so that a counter profile of this command can be scaled")
     ap.add_argument("--cpu-rows", type=int, default=0)
-    ap.add_argument("--algo", choices=["bidir", "unidir"], default="bidir",
+    ap.add_argument("--algo", choices=["bidir", "unidir", "bidir_diag"], default="bidir",
                     help="bidir: Algorithm 2 (the headline); unidir: Algorithm 1, the paper's "
-                         "baseline (no downlink compression, no server residual)")
+                         "baseline (no downlink compression, no server residual); bidir_diag: "
+                         "Algorithm 2 plus the per-step rho / rho_hat / 1-gamma estimates")
     ap.add_argument("--path", choices=["auto", "dense", "single"], default="auto",
                     help="select path: chosen by shape (default), dense multi-pass only, or "
                          "single-pass wherever the shape allows")
@@ -127,8 +128,15 @@ def main() -> int:
         msg_val = torch.zeros(N * cfg.K_up, dtype=torch.float32, device=dev)
         msg_cnt = torch.zeros(1, dtype=torch.int32, device=dev)
 
+    if args.algo == "bidir_diag":
+        ctx.enable_diagnostics()
+        diag = torch.zeros(8 + N, dtype=torch.float64, device=dev)
+
     def step(i):
-        if args.algo == "unidir":
+        if args.algo == "bidir_diag":
+            bts.bidir_step_diag(ctx, ring[i % n_buf], eps, delta, w, p, cfg.alpha, 1.0, up_idx,
+                                up_val, dn_idx, dn_val, diag)
+        elif args.algo == "unidir":
             bts.unidir_step(ctx, ring[i % n_buf], eps, w, p, cfg.alpha, 1.0, up_idx, up_val,
                             msg_idx, msg_val, msg_cnt)
         else:
@@ -184,8 +192,10 @@ def main() -> int:
             traffic = None
 
     out = {
-        "metric": "gradient coords/sec per bidirectional top-K step (N*d/s)" if args.algo == "bidir"
-        else "gradient coords/sec per unidirectional top-K step (N*d/s)",
+        "metric": {"bidir": "gradient coords/sec per bidirectional top-K step (N*d/s)",
+                   "unidir": "gradient coords/sec per unidirectional top-K step (N*d/s)",
+                   "bidir_diag": "gradient coords/sec per bidirectional top-K step with "
+                                 "rho/gamma diagnostics (N*d/s)"}[args.algo],
         "value": coords_per_s,
         "unit": "coords/s",
         "n_gpus": 1,
@@ -210,6 +220,10 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms": k_avg_ms, "launches": k_n},
     }
+    if args.algo == "bidir_diag":
+        dg = diag.cpu().tolist()
+        out["diagnostics_last_step"] = {"rho": dg[0], "rho_hat": dg[1],
+                                        "one_minus_gamma_max": dg[2], "nnz_fraction": dg[6]}
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or min(len(os.sched_getaffinity(0)), 16)
         out["cpu_baseline"] = cpu_baseline(cfg, ring[0], rows)

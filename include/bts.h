@@ -133,6 +133,29 @@ int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float*
                 uint32_t* dn_idx, float* dn_val, uint32_t* dn_count);
 
 /*
+ * bidir_step plus the per-step estimates of the constants the paper measures in its section
+ * on convergence-bound constants.  bts_enable_diagnostics allocates the extra scratch
+ * (2 d floats and O(N K_up) words) once; it is the only other allocation point of the library
+ * and needs K_up, K_dn >= 1.  bidir_step_diag queues one extra dense read of g and eps before
+ * the step and O(d + N K_up) work after it; state and messages come out exactly as from
+ * bidir_step.
+ * diag   8 + N doubles on the DEVICE:
+ *   [0] rho      = |Top_K(delta_{t-1} + sum_q p_q a^q) - Top_K(g_t)| / |alpha_in sum_q p_q g^q|
+ *                  (the two sides of Assumption 5; first Top_K with K_dn)
+ *   [1] rho_hat  = |Top_K(sum_q p_q a^q) - sum_q p_q Top_K(a^q)| / |alpha_in sum_q p_q g^q|
+ *                  (Assumption 6, the unidirectional counterpart; Top_K with K_up)
+ *   [2] max of 1 - gamma = |x - Top_K(x)|^2 / |x|^2 over the step's compressions
+ *   [3] |alpha_in sum_q p_q g^q|, [4] numerator of rho, [5] numerator of rho_hat
+ *   [6] distinct coordinates named by the uplinks / d (communication section)
+ *   [7] 1 - gamma of the server compression, [8 + q] 1 - gamma of worker q.
+ * The dense sums are fp32 fused multiply-add chains in ascending q; norms accumulate in fp64.
+ */
+int bts_enable_diagnostics(bts_ctx* ctx);
+int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
+                    const float* p, float alpha_in, float alpha_out, uint32_t* up_idx,
+                    float* up_val, uint32_t* dn_idx, float* dn_val, double* diag);
+
+/*
  * Timing of the dominant kernel (the dense pass over g and eps in topk_compress).  While
  * enabled, the library brackets that kernel with HIP events on the context's stream.
  * bts_profile_read synchronises those events and returns the summed kernel time in

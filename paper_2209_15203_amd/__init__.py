@@ -6,8 +6,8 @@ arguments (tensor pointers, the current HIP stream) and raises on error codes.  
 no CPU fallback: importing :mod:`paper_2209_15203_amd.binding` without the built library
 fails loudly.
 """
-from .binding import (BtsContext, BtsError, bidir_step, downlink_topk, lib_path, load_library,
+from .binding import (BtsContext, BtsError, bidir_step, bidir_step_diag, downlink_topk, lib_path, load_library,
                       sparse_aggregate, sparse_sgd_update, topk_compress, unidir_step)
 
-__all__ = ["BtsContext", "BtsError", "bidir_step", "downlink_topk", "lib_path", "load_library",
+__all__ = ["BtsContext", "BtsError", "bidir_step", "bidir_step_diag", "downlink_topk", "lib_path", "load_library",
            "sparse_aggregate", "sparse_sgd_update", "topk_compress", "unidir_step"]

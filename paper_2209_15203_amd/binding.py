@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libbts.so")
 
 EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
            "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
-           "unidir_step", "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path"]
+           "unidir_step", "bts_enable_diagnostics", "bidir_step_diag", "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path"]
 
 _lib = None
 
@@ -46,6 +46,8 @@ def load_library():
     lib.sparse_sgd_update.argtypes = [vp, vp, vp, u32, f32, vp]
     lib.bidir_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
     lib.unidir_step.argtypes = [vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
+    lib.bts_enable_diagnostics.argtypes = [vp]
+    lib.bidir_step_diag.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp]
     lib.bts_profile_enable.argtypes = [vp, C.c_int]
     lib.bts_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64)]
     lib.bts_last_path.argtypes = [vp, C.c_int, C.POINTER(u32), C.POINTER(u32)]
@@ -113,6 +115,9 @@ class BtsContext:
         self.check(self._lib.bts_profile_read(self._h, C.byref(ms), C.byref(n)), "bts_profile_read")
         return ms.value, n.value
 
+    def enable_diagnostics(self) -> None:
+        self.check(self._lib.bts_enable_diagnostics(self._h), "bts_enable_diagnostics")
+
     def set_path(self, mode: int) -> None:
         """0 = by shape, 1 = dense path only, 2 = single-pass path wherever possible."""
         self.check(self._lib.bts_set_path(self._h, int(mode)), "bts_set_path")
@@ -167,3 +172,14 @@ def unidir_step(ctx: BtsContext, g, eps, w, p, alpha_in: float, alpha_out: float
                                    _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val"),
                                    _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val"),
                                    _ptr(dn_count, U32, "dn_count")), "unidir_step")
+
+
+def bidir_step_diag(ctx: BtsContext, g, eps, delta, w, p, alpha_in: float, alpha_out: float,
+                    up_idx, up_val, dn_idx, dn_val, diag) -> None:
+    """diag: float64 tensor of 8 + N elements on the GPU."""
+    ctx.check(ctx._lib.bidir_step_diag(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"),
+                                       _ptr(delta, F32, "delta"), _ptr(w, F32, "w"),
+                                       _ptr(p, F32, "p"), alpha_in, alpha_out,
+                                       _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val"),
+                                       _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val"),
+                                       _ptr(diag, torch.float64, "diag")), "bidir_step_diag")

@@ -23,6 +23,8 @@ struct bts_ctx {
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
   uint32_t* agg_offsets;        // their exclusive scan (unidirectional message placement)
   uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
+  DiagScratch diag;             // allocated by bts_enable_diagnostics only
+  bool diag_ready;
   std::vector<void*> owned;     // every device allocation of the context
   // timing of the dominant kernel
   bool profile;
@@ -161,6 +163,8 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->agg_ranges = nullptr;
+  ctx->diag = DiagScratch{};
+  ctx->diag_ready = false;
   ctx->agg_offsets = nullptr;
   ctx->agg_start = ctx->agg_end = nullptr;
   if (hipGetDevice(&ctx->device) != hipSuccess) {
@@ -176,6 +180,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
             dev_alloc(ctx, &ctx->dense.state, (size_t)rows) &&
             dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
+            dev_alloc(ctx, &ctx->dense.tile_sums, (size_t)rows * 2 * dense_scan_tiles(nwc)) &&
             dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_ranges(d)) &&
             dev_alloc(ctx, &ctx->agg_offsets, (size_t)aggregate_ranges(d)) &&
             alloc_agg_tables(ctx) &&
@@ -257,6 +262,44 @@ int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float*
   hipError_t e = aggregate_update_unidirectional(
       ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, w, ctx->d, alpha_out, dn_idx,
       dn_val, dn_count, ctx->agg_ranges, ctx->agg_offsets, ctx->agg_start, ctx->agg_end);
+  return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
+}
+
+int bts_enable_diagnostics(bts_ctx* ctx) {
+  if (!ctx) return BTS_EINVAL;
+  if (ctx->diag_ready) return BTS_OK;
+  if (ctx->K_up == 0 || ctx->K_dn == 0) return BTS_EINVAL;
+  DiagScratch& ds = ctx->diag;
+  const size_t nk = (size_t)ctx->N * ctx->K_up;
+  bool ok = dev_alloc(ctx, &ds.u, (size_t)ctx->d) && dev_alloc(ctx, &ds.v, (size_t)ctx->d) &&
+            dev_alloc(ctx, &ds.part, diag_part_doubles((uint32_t)ctx->N)) &&
+            dev_alloc(ctx, &ds.a_idx, (size_t)ctx->K_dn) &&
+            dev_alloc(ctx, &ds.a_val, (size_t)ctx->K_dn) &&
+            dev_alloc(ctx, &ds.c_idx, (size_t)ctx->K_up) &&
+            dev_alloc(ctx, &ds.c_val, (size_t)ctx->K_up) && dev_alloc(ctx, &ds.m_idx, nk) &&
+            dev_alloc(ctx, &ds.m_val, nk) && dev_alloc(ctx, &ds.m_cnt, 1);
+  if (!ok) {
+    (void)hipGetLastError();
+    return BTS_ENOMEM;
+  }
+  ctx->diag_ready = true;
+  return BTS_OK;
+}
+
+int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
+                    const float* p, float alpha_in, float alpha_out, uint32_t* up_idx,
+                    float* up_val, uint32_t* dn_idx, float* dn_val, double* diag) {
+  if (!ctx || !diag || !g || !eps || !delta || !p) return BTS_EINVAL;
+  if (!ctx->diag_ready || ctx->K_up == 0 || ctx->K_dn == 0) return BTS_EINVAL;
+  hipError_t e = diag_before_step(ctx->stream, ctx->diag, g, eps, delta, p, (uint32_t)ctx->N,
+                                  ctx->d, alpha_in);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  int rc = bidir_step(ctx, g, eps, delta, w, p, alpha_in, alpha_out, up_idx, up_val, dn_idx,
+                      dn_val, nullptr);
+  if (rc != BTS_OK) return rc;
+  e = diag_after_step(ctx->stream, ctx->diag, ctx->dense, eps, delta, p, (uint32_t)ctx->N, ctx->d,
+                      ctx->K_up, ctx->K_dn, alpha_in, up_idx, up_val, dn_idx, dn_val,
+                      ctx->agg_ranges, ctx->agg_offsets, ctx->agg_start, ctx->agg_end, diag);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 

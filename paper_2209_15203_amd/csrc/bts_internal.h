@@ -39,8 +39,10 @@ struct DenseScratch {
   SelState* state;    // rows
   uint32_t* cnt_gt;   // rows x nwc: per wave-chunk count of key > T, then exclusive offsets
   uint32_t* cnt_eq;   // rows x nwc: same for key == T
+  uint32_t* tile_sums;  // rows x 2 x dense_scan_tiles(nwc)
   uint32_t nwc;       // wave-chunks per row (upper bound, same for every row)
 };
+uint32_t dense_scan_tiles(uint32_t nwc);
 
 // ---- dense exact select (handles any input, any K in 1..d) ----------------------------
 // x: rows x d (row stride d).  If g != nullptr the first pass computes
@@ -109,6 +111,30 @@ hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx
                                            uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
                                            uint32_t* range_cnt, uint32_t* range_off,
                                            uint32_t* tab_start, uint32_t* tab_end);
+// ---- per-step diagnostics (rho, rho_hat, 1 - gamma, nnz fraction) -------------------------
+struct DiagScratch {
+  float* u;          // d: sum_q p_q a^q
+  float* v;          // d: delta_{t-1} + sum_q p_q a^q
+  double* part;      // diag_part_doubles(N) partial sums
+  uint32_t* a_idx;   // K_dn: Top_K(v)
+  float* a_val;
+  uint32_t* c_idx;   // K_up: Top_K(u)
+  float* c_val;
+  uint32_t* m_idx;   // N*K_up: sum_q p_q Top_K(a^q), sparse
+  float* m_val;
+  uint32_t* m_cnt;
+};
+size_t diag_part_doubles(uint32_t N);
+hipError_t diag_before_step(hipStream_t s, const DiagScratch& ds, const float* g,
+                            const float* eps, const float* delta, const float* p, uint32_t N,
+                            uint64_t d, float alpha);
+hipError_t diag_after_step(hipStream_t s, const DiagScratch& ds, const DenseScratch& dense,
+                           const float* eps, const float* delta, const float* p, uint32_t N,
+                           uint64_t d, uint32_t K_up, uint32_t K_dn, float alpha,
+                           const uint32_t* up_idx, const float* up_val, const uint32_t* dn_idx,
+                           const float* dn_val, uint32_t* agg_cnt, uint32_t* agg_off,
+                           uint32_t* tab_start, uint32_t* tab_end, double* diag);
+
 hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint32_t K,
                       float alpha_out, float* w, uint64_t d);
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v);

@@ -155,28 +155,62 @@ __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, u
   }
 }
 
-// Exclusive scan of the per-chunk counts of one row, in place.  One block of 1024 threads
-// per row; thread t owns a contiguous slice of the chunks.
+// Exclusive scan of the per-chunk counts of every row, in place, in two levels: sums of
+// tiles of kScanTile chunks, then each tile scanned from the sum of the tiles before it.
+constexpr uint32_t kScanTile = 4096;
+
+__global__ __launch_bounds__(1024) void k_tile_sums(const uint32_t* __restrict__ cnt_gt,
+                                                    const uint32_t* __restrict__ cnt_eq,
+                                                    uint32_t nwc, uint32_t ntiles,
+                                                    uint32_t* __restrict__ tile_sums,
+                                                    RowMask need) {
+  __shared__ uint32_t lds[1024 / kWave + 1];
+  const uint32_t row = blockIdx.y, tile = blockIdx.x;
+  if (!row_needed(need, row)) return;
+  const uint32_t b = tile * kScanTile, e = min(b + kScanTile, nwc);
+#pragma unroll 1
+  for (int which = 0; which < 2; ++which) {
+    const uint32_t* a = (which == 0 ? cnt_gt : cnt_eq) + (uint64_t)row * nwc;
+    uint32_t s = 0;
+    for (uint32_t i = b + threadIdx.x; i < e; i += blockDim.x) s += a[i];
+    uint32_t total;
+    (void)block_exclusive_scan(s, lds, &total);
+    if (threadIdx.x == 0) tile_sums[((uint64_t)row * 2 + which) * ntiles + tile] = total;
+  }
+}
+
 __global__ __launch_bounds__(1024) void k_scan_chunks(uint32_t* __restrict__ cnt_gt,
                                                       uint32_t* __restrict__ cnt_eq,
-                                                      uint32_t nwc, RowMask need) {
+                                                      uint32_t nwc, uint32_t ntiles,
+                                                      const uint32_t* __restrict__ tile_sums,
+                                                      RowMask need) {
   __shared__ uint32_t lds[1024 / kWave + 1];
-  const uint32_t row = blockIdx.x;
+  const uint32_t row = blockIdx.y, tile = blockIdx.x;
   if (!row_needed(need, row)) return;
-  const uint32_t per = (nwc + blockDim.x - 1) / blockDim.x;
-  const uint32_t b = threadIdx.x * per;
-  const uint32_t e = min(b + per, nwc);
+  const uint32_t b = tile * kScanTile, e = min(b + kScanTile, nwc);
+  constexpr uint32_t kPer = kScanTile / 1024;        // consecutive chunks per thread
 #pragma unroll 1
   for (int which = 0; which < 2; ++which) {
     uint32_t* a = (which == 0 ? cnt_gt : cnt_eq) + (uint64_t)row * nwc;
+    const uint32_t* ts = tile_sums + ((uint64_t)row * 2 + which) * ntiles;
+    uint32_t before = 0;
+    for (uint32_t t = threadIdx.x; t < tile; t += blockDim.x) before += ts[t];
+    uint32_t base;
+    (void)block_exclusive_scan(before, lds, &base);  // base = sum over the earlier tiles
+    uint32_t v[kPer];
     uint32_t s = 0;
-    for (uint32_t i = b; i < e; ++i) s += a[i];
+    const uint32_t i0 = b + threadIdx.x * kPer;
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+      v[k] = i0 + k < e ? a[i0 + k] : 0u;
+      s += v[k];
+    }
     uint32_t total;
-    uint32_t run = block_exclusive_scan(s, lds, &total);
-    for (uint32_t i = b; i < e; ++i) {
-      const uint32_t t = a[i];
-      a[i] = run;
-      run += t;
+    uint32_t run = base + block_exclusive_scan(s, lds, &total);
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+      if (i0 + k < e) a[i0 + k] = run;
+      run += v[k];
     }
   }
 }
@@ -257,6 +291,8 @@ __global__ void k_fill(uint32_t* p, uint64_t n, uint32_t v) {
 
 }  // namespace
 
+uint32_t dense_scan_tiles(uint32_t nwc) { return (nwc + kScanTile - 1) / kScanTile; }
+
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v) {
   if (n == 0) return hipSuccess;
   k_fill<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, n, v);
@@ -279,12 +315,15 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
                         float* out_val, RowMask need, bool first_pass_done,
                         hipEvent_t ev0, hipEvent_t ev1) {
   const uint32_t nwc = sc.nwc;
-  // One wave per chunk when the path is the primary one.  As a gated fallback most rows
-  // leave at once, so a small grid whose blocks loop over the chunks keeps the cost of
-  // the idle launches down.
+  // A bounded grid whose blocks loop over the chunks: every block flushes its LDS histogram
+  // to the row's global histogram with atomics that are served at the memory side and
+  // serialise per address, so few fat blocks beat many thin ones; and as a gated fallback
+  // most rows leave at once, which keeps idle launches cheap.
   uint32_t gx = (nwc + kWavesPerBlock - 1) / kWavesPerBlock;
-  if (need != nullptr) {
-    const uint32_t lim = rows >= 4096 ? 1u : 4096u / rows;
+  {
+    uint32_t lim = 4096u / rows;
+    if (lim < 64u && need == nullptr) lim = 64u;
+    if (lim < 1u) lim = 1u;
     if (gx > lim) gx = lim;
   }
   const dim3 grid(gx, rows);
@@ -314,7 +353,12 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   BTS_LAUNCH_CHECK();
   k_count<<<grid, block, 0, s>>>(x, d, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need);
   BTS_LAUNCH_CHECK();
-  k_scan_chunks<<<dim3(rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, need);
+  const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
+  k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
+                                                        sc.tile_sums, need);
+  BTS_LAUNCH_CHECK();
+  k_scan_chunks<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
+                                                          sc.tile_sums, need);
   BTS_LAUNCH_CHECK();
   k_emit<<<grid, block, 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, out_idx, out_val,
                                 need);

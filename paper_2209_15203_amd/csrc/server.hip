@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
         msg_idx[pos] = (uint32_t)c0 + rel;
         msg_val[pos] = gt;
       }
-      dense[c0 + rel] = __fmaf_rn(neg_alpha, gt, dense[c0 + rel]);
+      if (dense != nullptr) dense[c0 + rel] = __fmaf_rn(neg_alpha, gt, dense[c0 + rel]);
       ++pos;
     }
   }

@@ -1,0 +1,101 @@
+"""GPU parity of bidir_step_diag: state and messages bit for bit as bidir_step, and the
+per-step estimates of rho, rho_hat, 1-gamma and the nnz fraction against the oracle.
+
+Tolerance of the estimates: the Top_K decisions behind them are taken on fp32 vectors that
+both sides build with the same fused multiply-add chains, so they select the same
+coordinates; what differs is only the order in which fp64 sums of n <= 2*10^6 squares are
+associated, bounded by n * 2^-53 < 3e-10 relative.  The tests use 1e-9."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-9
+SMALL = {"C1": 70_001, "C2": 120_002, "C3": 90_008, "C4": 70_003, "C5": 150_000}
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_diagnostics_scaled_configs(oracle, name):
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS[name].scaled(SMALL[name], N=min(wl.CONFIGS[name].N, 16), steps=3)
+    N, d = cfg.N, cfg.d
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p = wl.p_weights(wl.CONFIGS[name])[:N].copy()
+    st = G.GpuState(N, d, cfg.K_up, cfg.K_dn, wl.weights0(cfg, "cpu").numpy(), p)
+    st.ctx.enable_diagnostics()
+    diag = torch.zeros(8 + N, dtype=torch.float64, device=D)
+    for t in range(1, 4):
+        g = src.step(t)
+        bts.bidir_step_diag(st.ctx, g, st.eps, st.delta, st.w, st.p, cfg.alpha, 1.0, st.up_idx,
+                            st.up_val, st.dn_idx, st.dn_val, diag)
+        torch.cuda.synchronize()
+        want = oracle.bidir_step_diag(g.cpu().numpy(), st.h_eps, st.h_delta, st.h_w, st.h_p,
+                                      cfg.K_up, cfg.K_dn, cfg.alpha, 1.0)
+        tag = f"{cfg.name} step {t}"
+        G.assert_same_bits(st.up_idx, want["up_idx"], f"{tag} up_idx")
+        G.assert_same_bits(st.up_val, want["up_val"], f"{tag} up_val")
+        G.assert_same_bits(st.eps, st.h_eps, f"{tag} eps")
+        G.assert_same_bits(st.dn_idx, want["dn_idx"], f"{tag} dn_idx")
+        G.assert_same_bits(st.dn_val, want["dn_val"], f"{tag} dn_val")
+        G.assert_same_bits(st.delta, st.h_delta, f"{tag} delta")
+        G.assert_same_bits(st.w, st.h_w, f"{tag} w")
+        got = diag.cpu().numpy()
+        assert np.allclose(got, want["diag"], rtol=RTOL, atol=0), (tag, got[:8], want["diag"][:8])
+        assert got[6] == want["diag"][6]                 # a count: exact
+        assert 0 < got[1] and got[2] <= 1.0
+
+
+def test_diagnostics_degenerate_cases(oracle):
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    D = G.dev()
+    rng = np.random.default_rng(40)
+    d = 5000
+    # one worker, no server residual: rho = rho_hat = 0 exactly
+    g = rng.standard_normal((1, d)).astype(np.float32)
+    st = G.GpuState(1, d, 50, 50, np.zeros(d, np.float32), np.ones(1, np.float32))
+    st.ctx.enable_diagnostics()
+    diag = torch.zeros(9, dtype=torch.float64, device=D)
+    bts.bidir_step_diag(st.ctx, torch.from_numpy(g).to(D), st.eps, st.delta, st.w, st.p, 0.5, 1.0,
+                        st.up_idx, st.up_val, st.dn_idx, st.dn_val, diag)
+    torch.cuda.synchronize()
+    got = diag.cpu().numpy()
+    assert got[0] == 0.0 and got[1] == 0.0 and 0.0 < got[2] <= (d - 50) / d
+    # diagnostics must be enabled first
+    ctx = bts.BtsContext(1, d, 50, 50)
+    with pytest.raises(bts.BtsError):
+        bts.bidir_step_diag(ctx, torch.from_numpy(g).to(D), st.eps, st.delta, st.w, st.p, 0.5,
+                            1.0, st.up_idx, st.up_val, st.dn_idx, st.dn_val, diag)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["C1", "C3"])
+def test_diagnostics_full_size(oracle, name):
+    """Two steps at the benchmark's size; sums now run over up to 2.6*10^7 terms per row, so
+    the bound n * 2^-53 on the association error is 3e-9: tolerance 1e-8."""
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS[name]
+    N, d = cfg.N, cfg.d
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    st = G.GpuState(N, d, cfg.K_up, cfg.K_dn, wl.weights0(cfg, "cpu").numpy(), wl.p_weights(cfg))
+    st.ctx.enable_diagnostics()
+    diag = torch.zeros(8 + N, dtype=torch.float64, device=D)
+    for t in (1, 2):
+        g = src.step(t)
+        print(f"[{name} diagnostics] step {t}/2", flush=True)
+        bts.bidir_step_diag(st.ctx, g, st.eps, st.delta, st.w, st.p, cfg.alpha, 1.0, st.up_idx,
+                            st.up_val, st.dn_idx, st.dn_val, diag)
+        torch.cuda.synchronize()
+        want = oracle.bidir_step_diag(g.cpu().numpy(), st.h_eps, st.h_delta, st.h_w, st.h_p,
+                                      cfg.K_up, cfg.K_dn, cfg.alpha, 1.0)
+        G.assert_same_bits(st.eps, st.h_eps, f"{name} step {t} eps")
+        G.assert_same_bits(st.dn_idx, want["dn_idx"], f"{name} step {t} dn_idx")
+        G.assert_same_bits(st.w, st.h_w, f"{name} step {t} w")
+        got = diag.cpu().numpy()
+        assert np.allclose(got, want["diag"], rtol=1e-8, atol=0), (got[:8], want["diag"][:8])
