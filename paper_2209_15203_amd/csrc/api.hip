@@ -57,6 +57,7 @@ bool dev_alloc(bts_ctx* ctx, T** p, size_t count) {
 bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc) {
   if (!pl.enabled) return true;
   uint8_t* sel = nullptr;
+  uint64_t* sup = nullptr;
   bool ok = dev_alloc(ctx, &sc->sample_hist, (size_t)rows * 8192) &&
             dev_alloc(ctx, &sc->lower_key, rows) &&
             dev_alloc(ctx, &sc->cand_cnt, (size_t)rows * fast_sublists() * fast_counter_stride()) &&
@@ -64,10 +65,12 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
             dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_blocks() * 2048) &&
             dev_alloc(ctx, &sel, (size_t)rows * fast_sel_bytes()) &&
             dev_alloc(ctx, &sc->need, rows) &&
-            dev_alloc(ctx, &sc->bitmap, (size_t)rows * pl.words_per_row) &&
+            dev_alloc(ctx, &sc->bitmap_gt, (size_t)rows * pl.words_per_row) &&
+            dev_alloc(ctx, &sc->bitmap_eq, (size_t)rows * pl.words_per_row) &&
             dev_alloc(ctx, &sc->bucket_cnt, (size_t)rows * pl.nbk) &&
-            dev_alloc(ctx, &sc->bucket_off, (size_t)rows * pl.nbk);
+            dev_alloc(ctx, &sup, (size_t)rows * pl.nsup);
   sc->sel = sel;
+  sc->super_cnt = sup;
   return ok;
 }
 

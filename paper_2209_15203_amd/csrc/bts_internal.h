@@ -64,22 +64,24 @@ struct FastPlan {
   bool preferred;          // the default choice for this shape
   uint32_t stride;         // every stride-th 256-coordinate slice is sampled
   uint32_t target;         // sampled coordinates wanted at or above the lower bound
-  uint32_t cap;            // capacity of one candidate sub-list
+  uint32_t cap;            // capacity of one candidate list
   uint32_t nbk;            // 4096-coordinate buckets per row
+  uint32_t nsup;           // super-buckets (256 buckets) per row
   uint64_t words_per_row;  // bitmap words per row
 };
 
 struct FastScratch {
   uint32_t* sample_hist;   // rows x 8192 (zero between calls)
   uint32_t* lower_key;     // rows
-  uint32_t* cand_cnt;      // rows x sub-lists, one counter per 128-byte line
-  uint2* cand;             // rows x sub-lists x cap (index, value bits)
+  uint32_t* cand_cnt;      // rows x lists, one counter per 128-byte line
+  uint2* cand;             // rows x lists x cap (index, value bits)
   uint32_t* hist;          // rows x fast_hist_blocks() x 2048 partial histograms
   void* sel;               // rows x fast_sel_bytes()
   uint32_t* need;          // rows: 1 = the dense path must redo this row
-  uint32_t* bitmap;        // rows x words_per_row (zero between calls)
-  uint32_t* bucket_cnt;    // rows x nbk (zero between calls)
-  uint32_t* bucket_off;    // rows x nbk
+  uint32_t* bitmap_gt;     // rows x words_per_row (zero between calls): key > T
+  uint32_t* bitmap_eq;     // rows x words_per_row (zero between calls): key == T
+  uint32_t* bucket_cnt;    // rows x nbk (cleared at the start of a call)
+  void* super_cnt;         // rows x nsup 64-bit words (rewritten by every call)
 };
 
 FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K);
