@@ -321,7 +321,7 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   // most rows leave at once, which keeps idle launches cheap.
   uint32_t gx = (nwc + kWavesPerBlock - 1) / kWavesPerBlock;
   {
-    uint32_t lim = 4096u / rows;
+    uint32_t lim = 2048u / rows;
     if (lim < 64u && need == nullptr) lim = 64u;
     if (lim < 1u) lim = 1u;
     if (gx > lim) gx = lim;

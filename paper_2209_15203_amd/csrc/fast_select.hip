@@ -632,7 +632,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   BTS_LAUNCH_CHECK();
   // enough waves to fill the chip, few enough that empty groups stay cheap
   const uint64_t buckets = (uint64_t)rows * pl.nbk;
-  const int group = buckets >= (64ull << 17) ? 64 : (buckets >= (8ull << 17) ? 8 : 1);
+  const int group = buckets >= (64ull << 16) ? 64 : (buckets >= (8ull << 14) ? 8 : 1);
   const uint32_t groups = (pl.nbk + group - 1) / group;
   const dim3 egrid((groups + kWavesPerBlock - 1) / kWavesPerBlock, rows);
 #define BTS_EMIT(G)                                                                          \
