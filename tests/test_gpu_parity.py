@@ -354,3 +354,98 @@ def test_misaligned_buffers_are_rejected(G):
         bts.downlink_topk(ctx, off, ui, uv)
     with pytest.raises(bts.BtsError):
         bts.topk_compress(ctx, off, torch.zeros(64, device=D), 1.0, ui, uv)
+
+
+def _fresh_state(cfg, D):
+    return dict(eps=torch.zeros((cfg.N, cfg.d), device=D), delta=torch.zeros(cfg.d, device=D),
+                w=wl.weights0(cfg, D), ui=torch.zeros((cfg.N, cfg.K_up), dtype=torch.int32, device=D),
+                uv=torch.zeros((cfg.N, cfg.K_up), device=D),
+                di=torch.zeros(cfg.K_dn, dtype=torch.int32, device=D),
+                dv=torch.zeros(cfg.K_dn, device=D))
+
+
+def _step(bts, ctx, st, g, p, alpha):
+    bts.bidir_step(ctx, g, st["eps"], st["delta"], st["w"], p, alpha, 1.0, st["ui"], st["uv"],
+                   st["di"], st["dv"], None)
+
+
+def test_resume_from_copied_state_and_path_switching(G, oracle):
+    """The state of the algorithm lives in the caller's buffers only: four steps in one go
+    equal two steps, a copy of (eps, delta, w) into new buffers and a NEW context, and two
+    more steps.  The first run also switches the select path every step, which checks that
+    each path leaves the shared scratch (bitmaps, counters, histograms) clean."""
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS["C3"].scaled(300_007, N=6, steps=4)
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p = torch.full((cfg.N,), 1.0 / cfg.N, device=D)
+    gs = [src.step(t) for t in range(1, 5)]
+    a = _fresh_state(cfg, D)
+    ctx = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn)
+    for t, mode in enumerate((SINGLE_PASS, DENSE, SINGLE_PASS, 0)):
+        ctx.set_path(mode)
+        _step(bts, ctx, a, gs[t], p, cfg.alpha)
+    b = _fresh_state(cfg, D)
+    ctx1 = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn)
+    ctx1.set_path(DENSE)
+    for t in range(2):
+        _step(bts, ctx1, b, gs[t], p, cfg.alpha)
+    torch.cuda.synchronize()
+    c = _fresh_state(cfg, D)
+    for k in ("eps", "delta", "w"):
+        c[k].copy_(b[k])
+    ctx1.close()
+    ctx2 = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn)
+    ctx2.set_path(SINGLE_PASS)
+    for t in range(2, 4):
+        _step(bts, ctx2, c, gs[t], p, cfg.alpha)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k].view(torch.int32), c[k].view(torch.int32)), k
+    # and against the oracle
+    h_eps = np.zeros((cfg.N, cfg.d), np.float32)
+    h_delta = np.zeros(cfg.d, np.float32)
+    h_w = wl.weights0(cfg, D).cpu().numpy().copy()      # the very buffer the GPU started from
+    for t in range(4):
+        oracle.bidir_step(gs[t].cpu().numpy(), h_eps, h_delta, h_w, p.cpu().numpy(), cfg.K_up,
+                          cfg.K_dn, cfg.alpha, 1.0)
+    G.assert_same_bits(a["eps"], h_eps, "eps")
+    G.assert_same_bits(a["delta"], h_delta, "delta")
+    G.assert_same_bits(a["w"], h_w, "w")
+
+
+def test_two_contexts_on_two_streams(G):
+    """Two independent problems queued on two HIP streams (default priority) at the same
+    time give the same bits as running them one after the other."""
+    import paper_2209_15203_amd as bts
+    D = G.dev()
+    cfgs = [wl.CONFIGS["C1"].scaled(400_003, N=5, steps=3), wl.CONFIGS["C4"].scaled(250_001, N=7, steps=3)]
+    streams = [torch.cuda.Stream(device=D), torch.cuda.Stream(device=D)]
+    serial, overlapped = [], []
+    for run in ("serial", "overlapped"):
+        states, ctxs, gsets, ps = [], [], [], []
+        for cfg in cfgs:
+            src = wl.GradientSource(cfg, D)
+            gsets.append([src.step(t) for t in (1, 2, 3)])
+            ps.append(torch.full((cfg.N,), 1.0 / cfg.N, device=D))
+            states.append(_fresh_state(cfg, D))
+        torch.cuda.synchronize()
+        for cfg, s in zip(cfgs, streams):
+            ctx = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn, stream=s)
+            ctx.set_path(SINGLE_PASS)
+            ctxs.append(ctx)
+        if run == "serial":
+            for i in range(2):
+                for t in range(3):
+                    _step(bts, ctxs[i], states[i], gsets[i][t], ps[i], 0.01)
+                streams[i].synchronize()
+        else:
+            for t in range(3):
+                for i in range(2):
+                    _step(bts, ctxs[i], states[i], gsets[i][t], ps[i], 0.01)
+            for s in streams:
+                s.synchronize()
+        (serial if run == "serial" else overlapped).extend(states)
+    for sa, sb in zip(serial, overlapped):
+        for k in sa:
+            assert torch.equal(sa[k].view(torch.int32), sb[k].view(torch.int32)), k
