@@ -18,6 +18,7 @@ struct bts_ctx {
   int device;
   int last_hip_error;
   DenseScratch dense;
+  bool dense_dirty;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
@@ -163,6 +164,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->ev_used = 0;
   ctx->path_mode = 0;
   ctx->dense = DenseScratch{};
+  ctx->dense_dirty = false;
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->agg_ranges = nullptr;
@@ -177,9 +179,11 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   const uint32_t rows = (uint32_t)N;
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
   ctx->dense.nwc = nwc;
+  ctx->dense.rows = rows;
+  ctx->dense.dirty = &ctx->dense_dirty;
   ctx->plan_up = fast_plan(rows, d, K_up);
   ctx->plan_dn = fast_plan(1, d, K_dn);
-  bool ok = dev_alloc(ctx, &ctx->dense.hist, (size_t)rows * kBins0) &&
+  bool ok = dev_alloc(ctx, &ctx->dense.hist, (size_t)rows * dense_row_hist_words()) &&
             dev_alloc(ctx, &ctx->dense.state, (size_t)rows) &&
             dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&

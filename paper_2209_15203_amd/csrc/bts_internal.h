@@ -25,9 +25,7 @@ constexpr int kBinsLo = 1024;             // second and third digit: bits 19..10
 
 // Per-row state of the exact radix select on the 31-bit magnitude key.
 struct SelState {
-  uint32_t prefix;   // key bits fixed so far (right aligned)
-  uint32_t k_rem;    // how many of the wanted K lie at or below the current bin
-  uint32_t T;        // exact K-th largest key (valid after the third digit)
+  uint32_t T;        // exact K-th largest key
   uint32_t r;        // how many coordinates with key == T are kept (lowest indices first)
 };
 
@@ -35,7 +33,9 @@ struct SelState {
 using RowMask = const uint32_t*;
 
 struct DenseScratch {
-  uint32_t* hist;     // rows x kBins0
+  uint32_t* hist;     // rows x dense_row_hist_words(): three digit histograms, zero between calls
+  bool* dirty;        // host flag: a call failed half way, clear the histograms first
+  uint32_t rows;      // rows the scratch was sized for
   SelState* state;    // rows
   uint32_t* cnt_gt;   // rows x nwc: per wave-chunk count of key > T, then exclusive offsets
   uint32_t* cnt_eq;   // rows x nwc: same for key == T
@@ -43,6 +43,7 @@ struct DenseScratch {
   uint32_t nwc;       // wave-chunks per row (upper bound, same for every row)
 };
 uint32_t dense_scan_tiles(uint32_t nwc);
+uint32_t dense_row_hist_words();
 
 // ---- dense exact select (handles any input, any K in 1..d) ----------------------------
 // x: rows x d (row stride d).  If g != nullptr the first pass computes

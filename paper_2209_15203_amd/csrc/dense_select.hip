@@ -1,5 +1,6 @@
 // Dense exact Top_K select: a three-digit (11 + 10 + 10 bit) radix select on the 31-bit
-// magnitude key with LDS histograms, followed by an ordered emission that needs no
+// magnitude key with LDS histograms (each kernel resolves the digits found so far from the
+// finished histograms at its start), followed by an ordered emission that needs no
 // atomics for placement: per-wave-chunk counts of (key > T) and (key == T), an exclusive
 // scan over the chunks of a row, and in-wave ballot/popcount prefix sums.  Ties at the
 // threshold go to the lowest indices.  Works for every input and every K in 1..d; it is
@@ -20,21 +21,98 @@ __device__ __forceinline__ bool row_needed(RowMask need, uint32_t row) {
   return need == nullptr || need[row] != 0;
 }
 
+// Each row has three global histograms (digit 0: 2048 bins, digits 1 and 2: 1024 bins), all
+// zero between calls.  A kernel that needs the digits found so far walks the finished
+// histograms itself at its start (every block, redundantly: a few thousand loads), which
+// saves a separate launch per digit.
+constexpr int kRowHist = kBins0 + 2 * kBinsLo;     // words of histogram per row
+
+// Walk an NB-bin histogram from the top bin down and find the bin holding the `want`-th
+// largest key; *above = keys in higher bins.  All threads of the block call this; the result
+// is returned to every thread.
+template <int NB>
+__device__ __forceinline__ uint32_t resolve_digit(const uint32_t* __restrict__ h, uint32_t want,
+                                                  uint32_t* lds, uint32_t* s_out,
+                                                  uint32_t* above) {
+  constexpr int BPT = NB / kBlock;
+  const int top = NB - 1 - (int)threadIdx.x * BPT;   // this thread's highest bin
+  uint32_t c[BPT];
+  uint32_t s = 0;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) {
+    c[i] = h[top - i];
+    s += c[i];
+  }
+  uint32_t total;
+  const uint32_t excl = block_exclusive_scan(s, lds, &total);   // count in higher bins
+  if (excl < want && want <= excl + s) {                         // exactly one thread
+    uint32_t acc = excl;
+    int bin = top;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) {
+      if (acc + c[i] >= want) {
+        bin = top - i;
+        break;
+      }
+      acc += c[i];
+    }
+    s_out[0] = (uint32_t)bin;
+    s_out[1] = acc;
+  }
+  __syncthreads();
+  const uint32_t bin = s_out[0];
+  *above = s_out[1];
+  __syncthreads();
+  return bin;
+}
+
+// The digits fixed by the finished histograms of the row: after `digits` of them the key
+// prefix (right aligned) and how many of the K wanted keys lie at or below the prefix's bin.
+struct Resolved {
+  uint32_t prefix, k_rem;
+};
+
+template <int DIGITS>
+__device__ __forceinline__ Resolved resolve_row(const uint32_t* __restrict__ hist_row, uint32_t K,
+                                                uint32_t* lds, uint32_t* s_out) {
+  Resolved r{0u, K};
+  uint32_t above;
+  if (DIGITS >= 1) {
+    const uint32_t b = resolve_digit<kBins0>(hist_row, r.k_rem, lds, s_out, &above);
+    r.prefix = b;
+    r.k_rem -= above;
+  }
+  if (DIGITS >= 2) {
+    const uint32_t b = resolve_digit<kBinsLo>(hist_row + kBins0, r.k_rem, lds, s_out, &above);
+    r.prefix = (r.prefix << 10) | b;
+    r.k_rem -= above;
+  }
+  if (DIGITS >= 3) {
+    const uint32_t b =
+        resolve_digit<kBinsLo>(hist_row + kBins0 + kBinsLo, r.k_rem, lds, s_out, &above);
+    r.prefix = (r.prefix << 10) | b;      // the exact K-th largest key T
+    r.k_rem -= above;                     // how many holders of T are kept
+  }
+  return r;
+}
+
 // Histogram of one digit of the key over every coordinate of the row whose higher digits
 // match the prefix found so far.
 template <int DIGIT, bool FMA>
 __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
                                                  float* __restrict__ x, uint64_t d, float alpha,
-                                                 const SelState* __restrict__ st,
-                                                 uint32_t* __restrict__ hist, uint32_t nwc,
-                                                 RowMask need) {
+                                                 uint32_t K, uint32_t* __restrict__ hist,
+                                                 uint32_t nwc, RowMask need) {
   constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
   __shared__ uint32_t sh[NB];
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  __shared__ uint32_t s_out[2];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
+  uint32_t* hist_row = hist + (uint64_t)row * kRowHist;
   for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
+  const uint32_t prefix = resolve_row<DIGIT>(hist_row, K, lds, s_out).prefix;
   __syncthreads();
-  const uint32_t prefix = DIGIT == 0 ? 0u : st[row].prefix;
   // Bin 0 is counted per lane: a sparse row (the server's g_t is mostly exact zeros) would
   // otherwise serialise the whole wave on one LDS address.
   uint32_t bin0 = 0;
@@ -68,68 +146,31 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
   }
   if (bin0) atomicAdd(&sh[0], bin0);
   __syncthreads();
-  uint32_t* h = hist + (uint64_t)row * kBins0;
+  uint32_t* h = hist_row + (DIGIT == 0 ? 0 : (DIGIT == 1 ? kBins0 : kBins0 + kBinsLo));
   for (int i = threadIdx.x; i < NB; i += kBlock) {
     const uint32_t v = sh[i];
     if (v) atomicAdd(&h[i], v);
   }
 }
 
-// Walk the histogram of one digit from the top bin down and fix that digit of the K-th
-// largest key.  One block per row.  Leaves the histogram zeroed for the next digit.
-template <int DIGIT>
-__global__ __launch_bounds__(kBlock) void k_scan_digit(uint32_t* __restrict__ hist,
-                                                       SelState* __restrict__ st, uint32_t K,
-                                                       RowMask need) {
-  constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
-  constexpr int BPT = NB / kBlock;
-  __shared__ uint32_t lds[kBlock / kWave + 1];
-  const uint32_t row = blockIdx.x;
-  if (!row_needed(need, row)) return;
-  uint32_t* h = hist + (uint64_t)row * kBins0;
-  const uint32_t k_rem = DIGIT == 0 ? K : st[row].k_rem;
-  const int top = NB - 1 - (int)threadIdx.x * BPT;   // this thread's highest bin
-  uint32_t c[BPT];
-  uint32_t s = 0;
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) {
-    c[i] = h[top - i];
-    s += c[i];
-    h[top - i] = 0;
-  }
-  uint32_t total;
-  const uint32_t excl = block_exclusive_scan(s, lds, &total);   // count in higher bins
-  if (excl < k_rem && k_rem <= excl + s) {                       // exactly one thread
-    uint32_t acc = excl;
-    int bin = top;
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) {
-      if (acc + c[i] >= k_rem) {
-        bin = top - i;
-        break;
-      }
-      acc += c[i];
-    }
-    const uint32_t prefix = DIGIT == 0 ? (uint32_t)bin : ((st[row].prefix << 10) | (uint32_t)bin);
-    st[row].prefix = prefix;
-    st[row].k_rem = k_rem - acc;
-    if (DIGIT == 2) {
-      st[row].T = prefix;
-      st[row].r = k_rem - acc;
-    }
-  }
-}
-
 // Per wave-chunk: how many coordinates lie strictly above the threshold key, how many
 // on it.
 __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, uint64_t d,
-                                                  const SelState* __restrict__ st,
+                                                  uint32_t K, const uint32_t* __restrict__ hist,
+                                                  SelState* __restrict__ st,
                                                   uint32_t* __restrict__ cnt_gt,
                                                   uint32_t* __restrict__ cnt_eq, uint32_t nwc,
                                                   RowMask need) {
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  __shared__ uint32_t s_out[2];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
-  const uint32_t T = st[row].T;
+  const Resolved res = resolve_row<3>(hist + (uint64_t)row * kRowHist, K, lds, s_out);
+  const uint32_t T = res.prefix;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {       // for the emission kernel
+    st[row].T = T;
+    st[row].r = res.k_rem;
+  }
   for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
        wc += gridDim.x * kWavesPerBlock) {
   const ChunkGeom c = wave_chunk(d, row, wc);
@@ -224,9 +265,12 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
                                                  const uint32_t* __restrict__ off_gt,
                                                  const uint32_t* __restrict__ off_eq,
                                                  uint32_t nwc, uint32_t* __restrict__ out_idx,
-                                                 float* __restrict__ out_val, RowMask need) {
+                                                 float* __restrict__ out_val,
+                                                 uint32_t* __restrict__ hist, RowMask need) {
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
+  if (blockIdx.x == 0)                             // leave the row's histograms clear
+    for (int i = threadIdx.x; i < kRowHist; i += kBlock) hist[(uint64_t)row * kRowHist + i] = 0;
   const uint32_t T = st[row].T, r = st[row].r;
   for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
        wc += gridDim.x * kWavesPerBlock) {
@@ -310,10 +354,13 @@ hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uin
   return hipSuccess;
 }
 
+uint32_t dense_row_hist_words() { return kRowHist; }
+
 hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
                         float* out_val, RowMask need, bool first_pass_done,
                         hipEvent_t ev0, hipEvent_t ev1) {
+  const uint32_t rows_alloc = sc.rows;
   const uint32_t nwc = sc.nwc;
   // A bounded grid whose blocks loop over the chunks: every block flushes its LDS histogram
   // to the row's global histogram with atomics that are served at the memory side and
@@ -328,30 +375,27 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   }
   const dim3 grid(gx, rows);
   const dim3 block(kBlock);
-  hipError_t e = fill_u32(s, sc.hist, (uint64_t)rows * kBins0, 0);
-  if (e != hipSuccess) return e;
+  if (*sc.dirty) {                                 // an earlier call failed half way
+    hipError_t e = fill_u32(s, sc.hist, (uint64_t)rows_alloc * kRowHist, 0);
+    if (e != hipSuccess) return e;
+  }
+  *sc.dirty = true;                                // cleared when every launch went out
 
   const bool fuse = (g != nullptr) && !first_pass_done;
   if (fuse) {
     if (ev0) (void)hipEventRecord(ev0, s);
-    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, sc.state, sc.hist, nwc, need);
+    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, K, sc.hist, nwc, need);
     BTS_LAUNCH_CHECK();
     if (ev1) (void)hipEventRecord(ev1, s);
   } else {
-    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, nwc, need);
+    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need);
     BTS_LAUNCH_CHECK();
   }
-  k_scan_digit<0><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
+  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need);
   BTS_LAUNCH_CHECK();
-  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, nwc, need);
+  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need);
   BTS_LAUNCH_CHECK();
-  k_scan_digit<1><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
-  BTS_LAUNCH_CHECK();
-  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, sc.state, sc.hist, nwc, need);
-  BTS_LAUNCH_CHECK();
-  k_scan_digit<2><<<dim3(rows), block, 0, s>>>(sc.hist, sc.state, K, need);
-  BTS_LAUNCH_CHECK();
-  k_count<<<grid, block, 0, s>>>(x, d, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need);
+  k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need);
   BTS_LAUNCH_CHECK();
   const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
   k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
@@ -361,8 +405,9 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
                                                           sc.tile_sums, need);
   BTS_LAUNCH_CHECK();
   k_emit<<<grid, block, 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, out_idx, out_val,
-                                need);
+                                sc.hist, need);
   BTS_LAUNCH_CHECK();
+  *sc.dirty = false;
   return hipSuccess;
 }
 
