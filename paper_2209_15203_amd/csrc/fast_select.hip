@@ -547,9 +547,10 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.enabled = false;
   p.preferred = false;
   if (K == 0 || d < (1ull << 16) || (uint64_t)K * 64 > d) return p;
-  // Below about 16 M coordinates per call the step is bound by kernel launches and the
-  // dense path, with fewer launches, is the quicker one.
-  p.preferred = (uint64_t)rows * d >= (16ull << 20);
+  // Below about 25 M coordinates per call the step is bound by kernel launches and the
+  // dense path, with fewer launches, is the quicker one (measured: dense ahead at 24 M,
+  // single-pass ahead from 25.5 M on).
+  p.preferred = (uint64_t)rows * d >= 25000000ull;
   const uint64_t slices = d / 256;
   uint64_t stride = K / 64;        // about 128 of the sampled coordinates fall in the top 2K
   if (stride < 16) stride = 16;
