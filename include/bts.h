@@ -52,7 +52,9 @@ typedef struct bts_ctx bts_ctx;
  * use K_up == K_dn; its communication section treats them separately).  K == 0 and
  * K == d are legal.  hip_stream is a hipStream_t (host value, borrowed, may be null for
  * the default stream); every later call on the context queues onto it.  Scratch
- * (histograms, per-block counts, selection state) is sized here once.
+ * (histograms, per-block counts, candidate lists, bitmaps, selection state) is sized and
+ * cleared here once; the call synchronises the device before it returns (it is the only
+ * call besides bts_destroy, bts_profile_read and bts_last_path that does).
  */
 int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_dn,
                void* hip_stream);

@@ -190,13 +190,27 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
             dev_alloc(ctx, &ctx->dense.tile_sums, (size_t)rows * 2 * dense_scan_tiles(nwc)) &&
             dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_ranges(d)) &&
             dev_alloc(ctx, &ctx->agg_offsets, (size_t)aggregate_ranges(d)) &&
-            alloc_agg_tables(ctx) &&
-            alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up) &&
-            alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn);
+            alloc_agg_tables(ctx);
   if (!ok) {
     (void)hipGetLastError();
     release(ctx);
     return BTS_ENOMEM;
+  }
+  // The single-pass path is an optimisation: if its scratch does not fit, the dense path
+  // serves the shape alone.
+  if (!alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up)) {
+    (void)hipGetLastError();
+    ctx->plan_up.enabled = false;
+  }
+  if (!alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn)) {
+    (void)hipGetLastError();
+    ctx->plan_dn.enabled = false;
+  }
+  // The scratch was cleared with hipMemset on the null stream; the context's stream may be
+  // a non-blocking one that does not order itself after it.
+  if (hipDeviceSynchronize() != hipSuccess) {
+    release(ctx);
+    return BTS_EHIP;
   }
   *out = ctx;
   return BTS_OK;
@@ -289,6 +303,7 @@ int bts_enable_diagnostics(bts_ctx* ctx) {
     (void)hipGetLastError();
     return BTS_ENOMEM;
   }
+  if (hipDeviceSynchronize() != hipSuccess) return BTS_EHIP;   // see bts_create
   ctx->diag_ready = true;
   return BTS_OK;
 }
