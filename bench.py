@@ -70,6 +70,9 @@ def main() -> int:
                     help="bidir: Algorithm 2 (the headline); unidir: Algorithm 1, the paper's "
                          "baseline (no downlink compression, no server residual); bidir_diag: "
                          "Algorithm 2 plus the per-step rho / rho_hat / 1-gamma estimates")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step once per resident gradient batch into a HIP graph "
+                         "and time the replays (cuts kernel-launch overhead on small shapes)")
     ap.add_argument("--path", choices=["auto", "dense", "single"], default="auto",
                     help="select path: chosen by shape (default), dense multi-pass only, or "
                          "single-pass wherever the shape allows")
@@ -112,7 +115,8 @@ def main() -> int:
         ring.append(src.step(b + 1))
     torch.cuda.synchronize()
 
-    ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn)
+    side = torch.cuda.Stream(device=dev) if args.graph else None
+    ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn, stream=side)
     ctx.set_path({"auto": 0, "dense": 1, "single": 2}[args.path])
     eps = torch.zeros((N, d), dtype=torch.float32, device=dev)
     delta = torch.zeros(d, dtype=torch.float32, device=dev)
@@ -133,6 +137,9 @@ def main() -> int:
         diag = torch.zeros(8 + N, dtype=torch.float64, device=dev)
 
     def step(i):
+        if args.graph and graphs:
+            graphs[i % n_buf].replay()
+            return
         if args.algo == "bidir_diag":
             bts.bidir_step_diag(ctx, ring[i % n_buf], eps, delta, w, p, cfg.alpha, 1.0, up_idx,
                                 up_val, dn_idx, dn_val, diag)
@@ -142,6 +149,26 @@ def main() -> int:
         else:
             bts.bidir_step(ctx, ring[i % n_buf], eps, delta, w, p, cfg.alpha, 1.0, up_idx,
                            up_val, dn_idx, dn_val, None)
+
+    graphs = []
+    if args.graph:
+        # warm up eagerly on the side stream, then capture one graph per gradient batch;
+        # state is reset afterwards so the timed run starts from eps = delta = 0
+        with torch.cuda.stream(side):
+            step(0)
+        side.synchronize()
+        captured = []
+        for b in range(n_buf):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                step(b)
+            captured.append(gr)
+        graphs = captured
+        torch.cuda.synchronize()
+        eps.zero_()
+        delta.zero_()
+        w.copy_(wl.weights0(cfg, dev))
+        torch.cuda.synchronize()
 
     if args.calibrate_copy:
         src_c = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -172,6 +199,7 @@ def main() -> int:
 
     # dominant kernel: the dense pass over g and eps (12 algorithmic bytes per coordinate:
     # read g, read eps, write eps), timed with HIP events on the library's stream
+    graphs = []                          # the events are recorded by eager launches
     ctx.profile_enable(True)
     for _ in range(args.steps):
         step(it)
@@ -211,6 +239,7 @@ def main() -> int:
                                f"K_dn={cfg.K_dn}, {cfg.dist} gradients, fresh batch per step "
                                f"({n_buf} batches resident), residuals carried",
                    "alpha_in": cfg.alpha, "alpha_out": 1.0, "select_path": args.path,
+                   "hip_graph": bool(args.graph),
                    "uplink_rows_single_pass": rows_fast, "uplink_rows_dense": rows_dense},
         "hbm_gbps_algorithmic": b_alg / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac_algorithmic": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -123,6 +123,20 @@ def test_full_size_config(oracle, name):
 
 
 @pytest.mark.timeout(600)
+def test_full_size_dense_path_c3(oracle):
+    """The dense select path (the fallback of the single-pass path) forced at a benchmark
+    size: C3, one step, every output bit for bit against the oracle."""
+    import _gpu_util as G
+    cfg = wl.CONFIGS["C3"]
+    src = wl.GradientSource(cfg, G.dev())
+    w0 = wl.weights0(cfg, G.dev()).cpu().numpy()
+    st = G.GpuState(cfg.N, cfg.d, cfg.K_up, cfg.K_dn, w0, wl.p_weights(cfg))
+    st.ctx.set_path(1)
+    st.step_and_compare(oracle, src.step(1), cfg.alpha, 1.0, "C3 dense step 1")
+    assert st.ctx.last_path(0) == (0, cfg.N)
+
+
+@pytest.mark.timeout(600)
 def test_full_size_unidirectional_c3(oracle):
     """Algorithm 1 at a benchmark size (C3: 32 workers, d = 25,557,032): two steps, every
     output bit for bit against the oracle."""

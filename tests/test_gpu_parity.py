@@ -449,3 +449,52 @@ def test_two_contexts_on_two_streams(G):
     for sa, sb in zip(serial, overlapped):
         for k in sa:
             assert torch.equal(sa[k].view(torch.int32), sb[k].view(torch.int32)), k
+
+
+def test_bidir_step_replays_from_a_hip_graph(G, oracle):
+    """The step queues kernels only (no host synchronisation, no memset nodes), so it can be
+    captured once into a HIP graph and replayed.  Every replay, with fresh gradients copied
+    into the captured input buffer and ordinary eager work in between, must give the same
+    bits as the oracle."""
+    import paper_2209_15203_amd as bts
+    cfg = wl.CONFIGS["C2"].scaled(400_002, N=6, steps=5)
+    D = G.dev()
+    src = wl.GradientSource(cfg, D)
+    p_host = np.full(cfg.N, 1.0 / cfg.N, np.float32)
+    p = torch.from_numpy(p_host).to(D)
+    side = torch.cuda.Stream(device=D)
+    st = _fresh_state(cfg, D)
+    w0 = st["w"].cpu().numpy().copy()
+    g_static = torch.zeros((cfg.N, cfg.d), device=D)
+    ctx = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn, stream=side)
+    ctx.set_path(SINGLE_PASS)
+    h_eps = np.zeros((cfg.N, cfg.d), np.float32)
+    h_delta = np.zeros(cfg.d, np.float32)
+    h_w = w0
+    # one eager step first (warm-up outside the capture), checked like the replays
+    steps = [src.step(t) for t in range(1, 6)]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    for t, g in enumerate(steps):
+        g_static.copy_(g)
+        torch.cuda.synchronize()
+        if t == 0:
+            with torch.cuda.stream(side):
+                _step(bts, ctx, st, g_static, p, cfg.alpha)
+            side.synchronize()
+        elif t == 1:
+            with torch.cuda.graph(graph, stream=side):
+                _step(bts, ctx, st, g_static, p, cfg.alpha)
+            graph.replay()          # capture records, replay runs
+        else:
+            _ = (g_static * 2.0).sum().item()      # unrelated eager work between replays
+            graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.bidir_step(g.cpu().numpy(), h_eps, h_delta, h_w, p_host, cfg.K_up,
+                                 cfg.K_dn, cfg.alpha, 1.0)
+        G.assert_same_bits(st["ui"], want["up_idx"], f"replay {t} up_idx")
+        G.assert_same_bits(st["eps"], h_eps, f"replay {t} eps")
+        G.assert_same_bits(st["di"], want["dn_idx"], f"replay {t} dn_idx")
+        G.assert_same_bits(st["dv"], want["dn_val"], f"replay {t} dn_val")
+        G.assert_same_bits(st["delta"], h_delta, f"replay {t} delta")
+        G.assert_same_bits(st["w"], h_w, f"replay {t} w")
