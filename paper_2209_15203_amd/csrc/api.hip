@@ -19,11 +19,13 @@ struct bts_ctx {
   int last_hip_error;
   DenseScratch dense;
   bool dense_dirty;
+  bool fast_up_dirty, fast_dn_dirty;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
   uint32_t* agg_offsets;        // their exclusive scan (unidirectional message placement)
   uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
+  bool agg_tables_bad;          // a launch failed while the tables were in use: stop using them
   DiagScratch diag;             // allocated by bts_enable_diagnostics only
   bool diag_ready;
   std::vector<void*> owned;     // every device allocation of the context
@@ -40,8 +42,13 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int fail_hip(bts_ctx* ctx, hipError_t e) {
   ctx->last_hip_error = (int)e;
+  // the aggregation's tables are only clean if every launch that uses them went out
+  ctx->agg_tables_bad = true;
   return BTS_EHIP;
 }
+
+uint32_t* tab_start(const bts_ctx* ctx) { return ctx->agg_tables_bad ? nullptr : ctx->agg_start; }
+uint32_t* tab_end(const bts_ctx* ctx) { return ctx->agg_tables_bad ? nullptr : ctx->agg_end; }
 
 // Zero-filled device allocation owned by the context.
 template <typename T>
@@ -72,6 +79,7 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
             dev_alloc(ctx, &sup, (size_t)rows * pl.nsup);
   sc->sel = sel;
   sc->super_cnt = sup;
+  sc->rows = rows;
   return ok;
 }
 
@@ -165,6 +173,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->path_mode = 0;
   ctx->dense = DenseScratch{};
   ctx->dense_dirty = false;
+  ctx->fast_up_dirty = ctx->fast_dn_dirty = false;
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->agg_ranges = nullptr;
@@ -172,6 +181,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->diag_ready = false;
   ctx->agg_offsets = nullptr;
   ctx->agg_start = ctx->agg_end = nullptr;
+  ctx->agg_tables_bad = false;
   if (hipGetDevice(&ctx->device) != hipSuccess) {
     delete ctx;
     return BTS_EHIP;
@@ -198,6 +208,8 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   }
   // The single-pass path is an optimisation: if its scratch does not fit, the dense path
   // serves the shape alone.
+  ctx->fast_up.dirty = &ctx->fast_up_dirty;
+  ctx->fast_dn.dirty = &ctx->fast_dn_dirty;
   if (!alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up)) {
     (void)hipGetLastError();
     ctx->plan_up.enabled = false;
@@ -236,7 +248,7 @@ int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, 
   if (!ctx || !p || !delta) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
   hipError_t e = aggregate(ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, delta,
-                           ctx->d, union_nnz, ctx->agg_ranges, ctx->agg_start, ctx->agg_end);
+                           ctx->d, union_nnz, ctx->agg_ranges, tab_start(ctx), tab_end(ctx));
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -282,7 +294,7 @@ int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float*
   if (rc != BTS_OK) return rc;
   hipError_t e = aggregate_update_unidirectional(
       ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, w, ctx->d, alpha_out, dn_idx,
-      dn_val, dn_count, ctx->agg_ranges, ctx->agg_offsets, ctx->agg_start, ctx->agg_end);
+      dn_val, dn_count, ctx->agg_ranges, ctx->agg_offsets, tab_start(ctx), tab_end(ctx));
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -321,7 +333,7 @@ int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, floa
   if (rc != BTS_OK) return rc;
   e = diag_after_step(ctx->stream, ctx->diag, ctx->dense, eps, delta, p, (uint32_t)ctx->N, ctx->d,
                       ctx->K_up, ctx->K_dn, alpha_in, up_idx, up_val, dn_idx, dn_val,
-                      ctx->agg_ranges, ctx->agg_offsets, ctx->agg_start, ctx->agg_end, diag);
+                      ctx->agg_ranges, ctx->agg_offsets, tab_start(ctx), tab_end(ctx), diag);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 

@@ -83,6 +83,8 @@ struct FastScratch {
   uint32_t* bitmap_eq;     // rows x words_per_row (zero between calls): key == T
   uint32_t* bucket_cnt;    // rows x nbk (cleared at the start of a call)
   void* super_cnt;         // rows x nsup 64-bit words (rewritten by every call)
+  bool* dirty;             // host flag: a call failed half way, clear bitmaps and sample first
+  uint32_t rows;           // rows the scratch was sized for
 };
 
 FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K);

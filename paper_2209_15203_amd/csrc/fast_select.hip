@@ -579,6 +579,13 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
   const dim3 dense_grid((nwc + kStreamWaves - 1) / kStreamWaves, rows);
   unsigned long long* super_cnt = reinterpret_cast<unsigned long long*>(sc.super_cnt);
+  if (*sc.dirty) {       // an earlier call failed between marking and emission: clear the bits
+    hipError_t e = fill_u32(s, sc.bitmap_gt, (uint64_t)sc.rows * pl.words_per_row, 0);
+    if (e == hipSuccess) e = fill_u32(s, sc.bitmap_eq, (uint64_t)sc.rows * pl.words_per_row, 0);
+    if (e == hipSuccess) e = fill_u32(s, sc.sample_hist, (uint64_t)sc.rows * kSampleBins, 0);
+    if (e != hipSuccess) return e;
+  }
+  *sc.dirty = true;      // cleared when every launch of this call went out
   // 1. sample
   const uint64_t n_samp = (d / 256) / pl.stride + 1;
   uint32_t sample_blocks = (uint32_t)((n_samp + kWavesPerBlock * 8 - 1) / (kWavesPerBlock * 8));
@@ -648,6 +655,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
     BTS_EMIT(1);
 #undef BTS_EMIT
   BTS_LAUNCH_CHECK();
+  *sc.dirty = false;
   return hipSuccess;
 }
 
