@@ -368,9 +368,9 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   // most rows leave at once, which keeps idle launches cheap.
   uint32_t gx = (nwc + kWavesPerBlock - 1) / kWavesPerBlock;
   {
+    // at least 256 blocks per row, so that a lone row that falls back still streams fast
     uint32_t lim = 2048u / rows;
-    if (lim < 64u && need == nullptr) lim = 64u;
-    if (lim < 1u) lim = 1u;
+    if (lim < 256u) lim = 256u;
     if (gx > lim) gx = lim;
   }
   const dim3 grid(gx, rows);
