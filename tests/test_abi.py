@@ -60,3 +60,12 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libbts.so")
     with pytest.raises(binding.BtsError):
         binding.load_library()
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 without any HIP or C++."""
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text('#include "bts.h"\nint main(void) { return BTS_OK; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), "-fsyntax-only", str(src)], check=True)
