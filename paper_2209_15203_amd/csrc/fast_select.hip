@@ -22,8 +22,8 @@
 //                it is greater, or equal with fewer than r equal ones before it (lower index
 //                wins); its place in the message is #greater before + min(#equal before, r),
 //                which the walk gets from the super-bucket and bucket counters and
-//                popcounts.  It gathers the value from eps, stores +0 there and clears the
-//                bits.
+//                popcounts.  It writes the indices and clears the bits, then gathers the
+//                values from eps in parallel and stores +0 there.
 //
 // Steps 4-5 touch O(K) data.  Used for the worker compression (rows = N, fused with the
 // error compensation of Algorithm 2) and for the server compression (one row, no fusion).
@@ -485,52 +485,80 @@ __global__ __launch_bounds__(kBlock) void k_emit_bitmap(
   float* xr = x + (uint64_t)row * d;
   uint32_t* oi = out_idx + (uint64_t)row * K;
   float* ov = out_val + (uint64_t)row * K;
+  // the group's slice of the message
+  const uint32_t grp_gt0 = __shfl(my_gt0, 0, kWave), grp_eq0 = __shfl(my_eq0, 0, kWave);
+  const uint32_t grp_gt1 = grp_gt0 + __shfl(incl_gt, kWave - 1, kWave);
+  const uint32_t grp_eq1 = grp_eq0 + __shfl(incl_eq, kWave - 1, kWave);
+  const uint32_t p_first = grp_gt0 + min(grp_eq0, r);
+  const uint32_t p_end = min(grp_gt1 + min(grp_eq1, r), K);
+  // Part one writes the indices only.  The words of up to kBatch buckets are fetched before
+  // any of them is walked, so a wave waits for memory once per batch, not once per bucket.
+  constexpr int kBatch = GROUP < 8 ? GROUP : 8;
   while (live) {
-    const int src = __ffsll((unsigned long long)live) - 1;
-    live &= live - 1;
-    const uint32_t bk = first + src;
-    const uint32_t cnt = __shfl(my_cnt, src, kWave);
-    const uint64_t w0 = (uint64_t)bk * kBucketWords + 2u * lane_id();
-    uint32_t g0 = 0, g1 = 0, e0 = 0, e1 = 0;
-    if (cnt & 0xFFFFu) {
-      if (w0 < words_per_row) g0 = wg[w0];
-      if (w0 + 1 < words_per_row) g1 = wg[w0 + 1];
-    }
-    if (cnt >> 16) {
-      if (w0 < words_per_row) e0 = we[w0];
-      if (w0 + 1 < words_per_row) e1 = we[w0 + 1];
-    }
-    // per lane at most 64 bits of each kind: the packed scan cannot carry across halves
-    const uint32_t mine = (__popc(g0) + __popc(g1)) | ((__popc(e0) + __popc(e1)) << 16);
-    const uint32_t pre = wave_inclusive_scan(mine) - mine;
-    uint32_t n_gt = __shfl(my_gt0, src, kWave) + (pre & 0xFFFFu);   // greater before me
-    uint32_t n_eq = __shfl(my_eq0, src, kWave) + (pre >> 16);       // equal before me
+    int src[kBatch];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const uint32_t gb = half == 0 ? g0 : g1, eb = half == 0 ? e0 : e1;
-      uint32_t bits = gb | eb;
-      const uint32_t base = (uint32_t)((w0 + half) * 32u);
-      while (bits) {
-        const uint32_t t = __ffs(bits) - 1;
-        bits &= bits - 1;
-        const bool is_gt = (gb >> t) & 1u;
-        const uint32_t idx = base + t;
-        if (is_gt || n_eq < r) {
-          const uint32_t pos = n_gt + min(n_eq, r);
-          if (pos < K && idx < d) {
-            oi[pos] = idx;
-            ov[pos] = xr[idx];
-            xr[idx] = 0.0f;
-          }
-        }
-        n_gt += is_gt ? 1u : 0u;
-        n_eq += is_gt ? 0u : 1u;
+    for (int b = 0; b < kBatch; ++b) {
+      src[b] = live ? __ffsll((unsigned long long)live) - 1 : -1;
+      live &= live - 1;
+    }
+    uint32_t g0[kBatch], g1[kBatch], e0[kBatch], e1[kBatch];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      g0[b] = g1[b] = e0[b] = e1[b] = 0;
+      if (src[b] < 0) continue;
+      const uint32_t cnt = __shfl(my_cnt, src[b], kWave);
+      const uint64_t w0 = (uint64_t)(first + src[b]) * kBucketWords + 2u * lane_id();
+      if (cnt & 0xFFFFu) {
+        if (w0 < words_per_row) g0[b] = wg[w0];
+        if (w0 + 1 < words_per_row) g1[b] = wg[w0 + 1];
+      }
+      if (cnt >> 16) {
+        if (w0 < words_per_row) e0[b] = we[w0];
+        if (w0 + 1 < words_per_row) e1[b] = we[w0 + 1];
       }
     }
-    if (g0) wg[w0] = 0;
-    if (g1) wg[w0 + 1] = 0;
-    if (e0) we[w0] = 0;
-    if (e1) we[w0 + 1] = 0;
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      if (src[b] < 0) continue;
+      const uint64_t w0 = (uint64_t)(first + src[b]) * kBucketWords + 2u * lane_id();
+      // per lane at most 64 bits of each kind: the packed scan cannot carry across halves
+      const uint32_t mine =
+          (__popc(g0[b]) + __popc(g1[b])) | ((__popc(e0[b]) + __popc(e1[b])) << 16);
+      const uint32_t pre = wave_inclusive_scan(mine) - mine;
+      uint32_t n_gt = __shfl(my_gt0, src[b], kWave) + (pre & 0xFFFFu);   // greater before me
+      uint32_t n_eq = __shfl(my_eq0, src[b], kWave) + (pre >> 16);       // equal before me
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const uint32_t gb = half == 0 ? g0[b] : g1[b], eb = half == 0 ? e0[b] : e1[b];
+        uint32_t bits = gb | eb;
+        const uint32_t base = (uint32_t)((w0 + half) * 32u);
+        while (bits) {
+          const uint32_t t = __ffs(bits) - 1;
+          bits &= bits - 1;
+          const bool is_gt = (gb >> t) & 1u;
+          if (is_gt || n_eq < r) {
+            const uint32_t pos = n_gt + min(n_eq, r);
+            if (pos < K) oi[pos] = base + t;
+          }
+          n_gt += is_gt ? 1u : 0u;
+          n_eq += is_gt ? 0u : 1u;
+        }
+      }
+      if (g0[b]) wg[w0] = 0;
+      if (g1[b]) wg[w0 + 1] = 0;
+      if (e0[b]) we[w0] = 0;
+      if (e1[b]) we[w0 + 1] = 0;
+    }
+  }
+  // Part two: the values, one lane per entry of the group's slice.  The indices were stored
+  // by this wave; the workgroup-scope fence orders those stores before the loads.
+  __threadfence_block();
+  for (uint32_t p = p_first + lane_id(); p < p_end; p += kWave) {
+    const uint32_t idx = oi[p];
+    if (idx < d) {
+      ov[p] = xr[idx];
+      xr[idx] = 0.0f;
+    }
   }
 }
 
