@@ -52,7 +52,7 @@ typedef struct bts_ctx bts_ctx;
  * use K_up == K_dn; its communication section treats them separately).  K == 0 and
  * K == d are legal.  hip_stream is a hipStream_t (host value, borrowed, may be null for
  * the default stream); every later call on the context queues onto it.  Scratch
- * (histograms, per-block counts, candidate lists, bitmaps, selection state) is sized and
+ * (histograms, per-block counts, candidate lists, chunk directory, selection state) is sized and
  * cleared here once; the call synchronises the device before it returns (it is the only
  * call besides bts_destroy, bts_profile_read and bts_last_path that does).
  */

@@ -73,12 +73,10 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
             dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_blocks() * 2048) &&
             dev_alloc(ctx, &sel, (size_t)rows * fast_sel_bytes()) &&
             dev_alloc(ctx, &sc->need, rows) &&
-            dev_alloc(ctx, &sc->bitmap_gt, (size_t)rows * pl.words_per_row) &&
-            dev_alloc(ctx, &sc->bitmap_eq, (size_t)rows * pl.words_per_row) &&
-            dev_alloc(ctx, &sc->bucket_cnt, (size_t)rows * pl.nbk) &&
-            dev_alloc(ctx, &sup, (size_t)rows * pl.nsup);
+            dev_alloc(ctx, &sc->dir, (size_t)rows * pl.nwc_pad) &&
+            dev_alloc(ctx, &sup, (size_t)rows * pl.ntiles);
   sc->sel = sel;
-  sc->super_cnt = sup;
+  sc->tile_cnt = sup;
   sc->rows = rows;
   return ok;
 }

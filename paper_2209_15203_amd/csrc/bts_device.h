@@ -117,6 +117,7 @@ __device__ __forceinline__ void visit_chunk(const float* __restrict__ g, float* 
       f(e, v, 0xFu);
     }
   } else {
+#pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint64_t e = e0 + (uint64_t)u * (kWave * 4);
       float v[4];

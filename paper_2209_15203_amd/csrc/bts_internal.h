@@ -66,9 +66,8 @@ struct FastPlan {
   uint32_t stride;         // every stride-th 256-coordinate slice is sampled
   uint32_t target;         // sampled coordinates wanted at or above the lower bound
   uint32_t cap;            // capacity of one candidate list
-  uint32_t nbk;            // 4096-coordinate buckets per row
-  uint32_t nsup;           // super-buckets (256 buckets) per row
-  uint64_t words_per_row;  // bitmap words per row
+  uint32_t ntiles;         // directory tiles (64 wave chunks) per row
+  uint32_t nwc_pad;        // directory entries per row (ntiles * 64)
 };
 
 struct FastScratch {
@@ -79,11 +78,10 @@ struct FastScratch {
   uint32_t* hist;          // rows x fast_hist_blocks() x 2048 partial histograms
   void* sel;               // rows x fast_sel_bytes()
   uint32_t* need;          // rows: 1 = the dense path must redo this row
-  uint32_t* bitmap_gt;     // rows x words_per_row (zero between calls): key > T
-  uint32_t* bitmap_eq;     // rows x words_per_row (zero between calls): key == T
-  uint32_t* bucket_cnt;    // rows x nbk (cleared at the start of a call)
-  void* super_cnt;         // rows x nsup 64-bit words (rewritten by every call)
-  bool* dirty;             // host flag: a call failed half way, clear bitmaps and sample first
+  uint2* dir;              // rows x nwc_pad (zero between calls): per wave chunk the start
+                           // of its run in its list and the run's length
+  void* tile_cnt;          // rows x ntiles 64-bit words (rewritten by every call)
+  bool* dirty;             // host flag: a call failed half way, clear directory and sample first
   uint32_t rows;           // rows the scratch was sized for
 };
 

@@ -8,22 +8,22 @@
 //                alpha g is histogrammed on the top 13 bits of the magnitude key; a lower
 //                bound L is chosen so that about 2K coordinates of the row lie at or above it.
 //   2. stream:   the one dense pass computes a, stores it over eps and appends every
-//                coordinate with key >= L to the row's candidate lists (wave-aggregated
-//                atomic append; the order inside a list does not matter).
+//                coordinate with key >= L to the row's candidate lists: the hits of a wave
+//                chunk (512 coordinates) go, in index order, into one run of one list (one
+//                atomic add per chunk with hits), and the chunk notes where its run starts
+//                and how long it is in the row's chunk directory.
 //   3. verify:   if no list overflowed and the lists hold at least K entries, the K largest
 //                of the row are all listed.  Otherwise the row is flagged and the dense path
 //                (which reads the stored a again) redoes it.  The result never depends on L.
 //   4. select:   exact 11 + 10 + 10 bit radix select of the K-th largest key T over the
 //                lists, and r = how many holders of T are kept.
-//   5. emit:     candidates above T set a bit in the row's "greater" bitmap, holders of T in
-//                its "equal" bitmap, and bump the counter of their 4096-coordinate bucket; a
-//                small kernel sums the counters per 2^20-coordinate super-bucket.  One more
-//                kernel walks the non-empty buckets in index order: a coordinate is kept if
-//                it is greater, or equal with fewer than r equal ones before it (lower index
-//                wins); its place in the message is #greater before + min(#equal before, r),
-//                which the walk gets from the super-bucket and bucket counters and
-//                popcounts.  It writes the indices and clears the bits, then gathers the
-//                values from eps in parallel and stores +0 there.
+//   5. emit:     the directory in chunk order names the candidates in index order.  Count
+//                the entries greater than / equal to T per tile of 64 chunks, scan the
+//                tiles, then walk each tile again: an entry is kept if it is greater, or
+//                equal with fewer than r equal ones before it (lower index wins); its place
+//                in the message is #greater before + min(#equal before, r).  The pair comes
+//                from the list (no second read of eps), +0 is stored to eps there, and the
+//                directory entries are zeroed for the next call.
 //
 // Steps 4-5 touch O(K) data.  Used for the worker compression (rows = N, fused with the
 // error compensation of Algorithm 2) and for the server compression (one row, no fusion).
@@ -31,8 +31,8 @@
 // Two facts of this part shaped the kernels: atomics that return a value on one address are
 // served at the memory side at a few million per second, and a device-scope fence writes
 // back the XCD's L2.  Hence many append counters on separate 128-byte lines, one append per
-// wave chunk, per-block partial histograms with plain stores, and kernel boundaries instead
-// of last-block-done tickets.
+// wave chunk, per-block partial histograms with plain stores, kernel boundaries instead of
+// last-block-done tickets, and an emission that needs no atomics at all.
 
 #include "bts_device.h"
 
@@ -51,24 +51,17 @@ constexpr int kSliceUnroll = 8;
 constexpr uint32_t kSubLists = 64;
 constexpr uint32_t kCounterStride = 32;               // words between two counters
 constexpr uint32_t kMaxHistBlocks = 32;               // blocks per row in a candidate pass
-constexpr uint32_t kBucketShift = 12;                 // 4096 coordinates per bucket
-constexpr uint32_t kBucketWords = (1u << kBucketShift) / 32;   // 128 bitmap words
-constexpr uint32_t kSuperShift = 8;                   // 256 buckets per super-bucket
 
 // ---- 1. sample histogram ------------------------------------------------------------
 // Slices are cut at absolute multiples of 256 coordinates (16-byte aligned); only slices
-// that lie entirely inside the row are sampled.  The kernel also clears the row's bucket
-// counters, which the previous call's emission leaves set.
+// that lie entirely inside the row are sampled.
 template <bool FMA>
 __global__ __launch_bounds__(kBlock) void k_sample_hist(
     const float* __restrict__ g, const float* __restrict__ x, uint64_t d, float alpha,
-    uint32_t stride, uint32_t* __restrict__ shist, uint32_t* __restrict__ bucket_cnt,
-    uint32_t nbk) {
+    uint32_t stride, uint32_t* __restrict__ shist) {
   __shared__ uint32_t sh[kSampleBins];
   const uint32_t row = blockIdx.y;
   for (int i = threadIdx.x; i < kSampleBins; i += kBlock) sh[i] = 0;
-  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < nbk; i += gridDim.x * kBlock)
-    bucket_cnt[(uint64_t)row * nbk + i] = 0;
   __syncthreads();
   const uint64_t lo = (uint64_t)row * d, hi = lo + d;
   const uint64_t first = (lo + kSlice - 1) / kSlice;          // first whole slice
@@ -156,14 +149,53 @@ __global__ __launch_bounds__(kBlock) void k_pick_bound(uint32_t* __restrict__ sh
 // ---- 2. the dense pass ------------------------------------------------------------------
 // One wave per kWaveChunk coordinates.  Whole chunks take the fast body: kUnroll 16-byte
 // loads per lane and array in flight, fused multiply-add, store, compare against the
-// row's lower bound; the lanes' hits (rare) are ranked with one wave scan and appended
-// with ONE atomic add per chunk (to the chunk's list).  The partial chunks at the ends of
-// a row go slice by slice.
+// row's lower bound.  A chunk with hits (rare) ranks them in index order with one wave
+// scan, reserves room in its list with ONE atomic add, stores the entries there as one
+// run, and records (start of the run, length) in the row's chunk directory.  Chunks
+// without hits leave their directory entry alone (it is zero between calls).  The partial
+// chunks at the ends of a row load element by element and append the same way.
+static_assert(kUnroll <= 2, "the packed per-slice counts below hold two 16-bit fields");
+
+// flags: bit 4u + j set = element j of the lane's slice u is a hit; v: the lane's values;
+// i0: index in the row of the lane's first element of slice 0 (modulo 2^32 for lanes that
+// start before the row).  All lanes of the wave call this together.
+__device__ __forceinline__ void append_run(uint32_t flags, const float (&v)[kUnroll][4],
+                                           uint32_t i0, uint32_t* counter, uint2* list,
+                                           uint32_t cap, uint2* dir_entry) {
+  if (__ballot(flags != 0) == 0) return;
+  uint32_t mine = 0;                          // hits of slice u in bits 16u .. 16u + 15
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) mine |= (uint32_t)__popc((flags >> (4 * u)) & 0xFu) << (16 * u);
+  const uint32_t incl = wave_inclusive_scan(mine);          // a slice has 256 elements: no carry
+  const uint32_t tot = __shfl(incl, kWave - 1, kWave);
+  const uint32_t total = (tot & 0xFFFFu) + (tot >> 16);
+  uint32_t base = 0;
+  if (lane_id() == 0) {
+    base = atomicAdd(counter, total);
+    *dir_entry = make_uint2(base, total);
+  }
+  base = __shfl(base, 0, kWave);
+  const uint32_t excl = incl - mine;
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    // index order: slice 0 of every lane, then slice 1
+    uint32_t pos = base + (u == 0 ? (excl & 0xFFFFu) : (tot & 0xFFFFu) + (excl >> 16));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (flags & (1u << (4 * u + j))) {
+        if (pos < cap)
+          list[pos] = make_uint2(i0 + (uint32_t)u * (kWave * 4) + j, __float_as_uint(v[u][j]));
+        ++pos;
+      }
+    }
+  }
+}
+
 template <bool FMA>
 __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
     const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
     const uint32_t* __restrict__ lower_key, uint32_t* __restrict__ cand_cnt,
-    uint2* __restrict__ cand, uint32_t cap) {
+    uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir, uint32_t nwc_pad) {
   const uint32_t row = blockIdx.y;
   const uint32_t wc = blockIdx.x * kStreamWaves + threadIdx.x / kWave;
   const ChunkGeom c = wave_chunk(d, row, wc);
@@ -172,8 +204,12 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
   const uint64_t sub = (uint64_t)row * kSubLists + wc % kSubLists;
   uint2* list = cand + sub * cap;                 // cap = capacity of one list
   uint32_t* counter = cand_cnt + sub * kCounterStride;
+  uint2* dir_entry = dir + (uint64_t)row * nwc_pad + wc;
+  const uint64_t e0 = c.base + (uint64_t)lane_id() * 4;
+  const uint32_t i0 = (uint32_t)(e0 - c.lo);
+  uint32_t flags = 0;
+  float v[kUnroll][4];
   if (c.full) {
-    const uint64_t e0 = c.base + (uint64_t)lane_id() * 4;
     f4 xv[kUnroll];
     f4 gv[kUnroll];
 #pragma unroll
@@ -182,7 +218,6 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
       xv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(x + e));
       if (FMA) gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
     }
-    uint32_t flags = 0;                       // bit 4u + j: element j of slice u is a hit
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint64_t e = e0 + (uint64_t)u * (kWave * 4);
@@ -193,54 +228,25 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
         xv[u].w = __fmaf_rn(alpha, gv[u].w, xv[u].w);
         __builtin_nontemporal_store(xv[u], reinterpret_cast<f4*>(x + e));
       }
-      flags |= (key_of(xv[u].x) >= L ? 1u : 0u) << (4 * u);
-      flags |= (key_of(xv[u].y) >= L ? 2u : 0u) << (4 * u);
-      flags |= (key_of(xv[u].z) >= L ? 4u : 0u) << (4 * u);
-      flags |= (key_of(xv[u].w) >= L ? 8u : 0u) << (4 * u);
-    }
-    if (__ballot(flags != 0) == 0) return;
-    const uint32_t mine = __popc(flags);
-    const uint32_t incl = wave_inclusive_scan(mine);
-    const uint32_t total = __shfl(incl, kWave - 1, kWave);
-    uint32_t base = 0;
-    if (lane_id() == 0) base = atomicAdd(counter, total);
-    base = __shfl(base, 0, kWave);
-    uint32_t pos = base + incl - mine;
-    const uint32_t i0 = (uint32_t)(e0 - c.lo);
+      v[u][0] = xv[u].x;
+      v[u][1] = xv[u].y;
+      v[u][2] = xv[u].z;
+      v[u][3] = xv[u].w;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const float v[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+      for (int j = 0; j < 4; ++j) flags |= (key_of(v[u][j]) >= L ? 1u : 0u) << (4 * u + j);
+    }
+  } else {
+    int u = 0;
+    visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t, const float (&vv)[4], uint32_t mask) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        if (flags & (1u << (4 * u + j))) {
-          if (pos < cap)
-            list[pos] = make_uint2(i0 + (uint32_t)u * (kWave * 4) + j, __float_as_uint(v[j]));
-          ++pos;
-        }
+        v[u][j] = vv[j];
+        flags |= (((mask >> j) & 1u) && key_of(vv[j]) >= L ? 1u : 0u) << (4 * u + j);
       }
-    }
-    return;
+      ++u;
+    });
   }
-  visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t e, const float (&v)[4], uint32_t mask) {
-    uint32_t flags = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      flags |= ((mask >> j) & 1u) && key_of(v[j]) >= L ? (1u << j) : 0u;
-    if (__ballot(flags != 0) == 0) return;
-    uint32_t total;
-    const uint32_t pre = wave_exclusive_small(__popc(flags), &total);
-    uint32_t base = 0;
-    if (lane_id() == 0) base = atomicAdd(counter, total);
-    base = __shfl(base, 0, kWave);
-    uint32_t pos = base + pre;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (flags & (1u << j)) {
-        if (pos < cap) list[pos] = make_uint2((uint32_t)(e + j - c.lo), __float_as_uint(v[j]));
-        ++pos;
-      }
-    }
-  });
+  append_run(flags, v, i0, counter, list, cap, dir_entry);
 }
 
 // ---- 3 + 4. verify and select on the candidate lists -------------------------------------
@@ -358,206 +364,173 @@ __global__ __launch_bounds__(kBlock) void k_cand_scan(const uint32_t* __restrict
   }
 }
 
-// ---- 5. ordered emission through two bitmaps ---------------------------------------------
-// Bucket counter: "greater" count in the low 16 bits, "equal" count in the high 16 bits (a
-// bucket holds 4096 coordinates, so neither half overflows).  Super-bucket counter: the same
-// two counts in the halves of a 64-bit word.
+// ---- 5. ordered emission through the chunk directory -------------------------------------
+// The directory lists a row's runs in chunk order, and a run holds its entries in index
+// order, so walking the directory visits the row's candidates in index order; nothing has
+// to be sorted and no atomics are needed.  A wave owns a tile of 64 consecutive chunks
+// (chunk wc appends to list wc % 64, so lane l's chunk always uses list l): it scans the
+// run lengths, then its lanes take the tile's entries round-robin in that order, finding
+// an entry's run by bisection on the scanned lengths.
 //
-// Consecutive entries of a list mostly come from one wave chunk of the dense pass, in index
-// order, so neighbouring lanes usually share a bucket: the lanes of a run add their counts
-// with one atomic by the run's first lane.
-__global__ __launch_bounds__(kBlock) void k_mark(const uint2* __restrict__ cand,
-                                                 const uint32_t* __restrict__ cand_cnt,
-                                                 uint32_t cap, const FastSel* __restrict__ sel,
-                                                 const uint32_t* __restrict__ need,
-                                                 uint32_t* __restrict__ bm_gt,
-                                                 uint32_t* __restrict__ bm_eq,
-                                                 uint64_t words_per_row,
-                                                 uint32_t* __restrict__ bucket_cnt,
-                                                 uint32_t nbk) {
+//   k_dir_count: per tile, how many entries are greater than T and how many equal T.
+//   k_dir_scan:  per row, exclusive prefix of those pairs over the tiles.
+//   k_dir_emit:  per tile again: an entry is kept if it is greater, or equal with fewer
+//                than r equal ones before it (lower index wins); its place in the message
+//                is #greater before + min(#equal before, r).  Writes the pair, stores +0 to
+//                x there and zeroes the tile's directory entries (also for rows that the
+//                dense path redoes).
+constexpr uint32_t kTileChunks = kWave;
+constexpr int kEmitUnroll = 4;                // entries per lane in flight
+
+struct TileView {
+  uint32_t total;          // entries in the tile
+  const uint32_t* off;     // per chunk: entries before it in the tile (LDS, this wave's)
+  const uint32_t* start;   // per chunk: start of its run in its list (LDS, this wave's)
+};
+
+// Loads the tile's directory entries (one per lane) and publishes the scanned lengths to
+// the wave's part of LDS.  *mine gets the lane's run length.
+__device__ __forceinline__ TileView load_tile(const uint2* __restrict__ dir_row, uint32_t tile,
+                                              uint32_t* lds_off, uint32_t* lds_start,
+                                              uint32_t* mine) {
+  const uint2 ent = dir_row[(uint64_t)tile * kTileChunks + lane_id()];
+  const uint32_t incl = wave_inclusive_scan(ent.y);
+  lds_off[lane_id()] = incl - ent.y;
+  lds_start[lane_id()] = ent.x;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  *mine = ent.y;
+  TileView t;
+  t.total = __shfl(incl, kWave - 1, kWave);
+  t.off = lds_off;
+  t.start = lds_start;
+  return t;
+}
+
+// Entry e (0 <= e < total) of the tile, in index order.
+__device__ __forceinline__ uint2 tile_entry(const TileView& t, uint32_t e,
+                                            const uint2* __restrict__ cand_row, uint32_t cap) {
+  uint32_t c = 0;                              // the last chunk with off[c] <= e
+#pragma unroll
+  for (uint32_t s = kTileChunks / 2; s > 0; s >>= 1)
+    if (t.off[c + s] <= e) c += s;
+  return cand_row[(uint64_t)c * cap + t.start[c] + (e - t.off[c])];
+}
+
+__global__ __launch_bounds__(kBlock) void k_dir_count(
+    const uint2* __restrict__ dir, uint32_t nwc_pad, const uint2* __restrict__ cand,
+    uint32_t cap, const FastSel* __restrict__ sel, const uint32_t* __restrict__ need,
+    unsigned long long* __restrict__ tile_cnt, uint32_t ntiles) {
+  __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
   const uint32_t row = blockIdx.y;
   if (need[row]) return;
+  const uint32_t w = threadIdx.x / kWave;
+  const uint32_t tile = blockIdx.x * kWavesPerBlock + w;
+  if (tile >= ntiles) return;
+  uint32_t mine;
+  const TileView t =
+      load_tile(dir + (uint64_t)row * nwc_pad, tile, s_off[w], s_start[w], &mine);
   const uint32_t T = sel[row].T;
-  const uint64_t sub = (uint64_t)row * kSubLists + blockIdx.x % kSubLists;
-  const uint32_t cnt = cand_cnt[sub * kCounterStride];
-  const uint2* list = cand + sub * cap;
-  const uint32_t part = blockIdx.x / kSubLists, parts = gridDim.x / kSubLists;
-  uint32_t* bc = bucket_cnt + (uint64_t)row * nbk;
-  const int lane = lane_id();
-  // whole waves stay in the loop together (the run logic uses wave-wide shuffles)
-  const uint32_t rounds = (cnt + parts * kBlock - 1) / (parts * kBlock);
-  for (uint32_t it = 0; it < rounds; ++it) {
-    const uint32_t j = (it * parts + part) * kBlock + threadIdx.x;
-    uint32_t bk = 0xFFFFFFFFu, val = 0;
-    if (j < cnt) {
-      const uint2 en = list[j];
-      const uint32_t idx = en.x, key = en.y & 0x7FFFFFFFu;
-      if (key >= T) {
-        const bool eq = key == T;
-        uint32_t* bm = (eq ? bm_eq : bm_gt) + (uint64_t)row * words_per_row;
-        atomicOr(&bm[idx >> 5], 1u << (idx & 31u));
-        bk = idx >> kBucketShift;
-        val = eq ? 0x10000u : 1u;
-      }
+  const uint2* cand_row = cand + (uint64_t)row * kSubLists * cap;
+  uint32_t gt = 0, eq = 0;
+  for (uint32_t e0 = 0; e0 < t.total; e0 += kWave * kEmitUnroll) {
+    uint32_t key[kEmitUnroll];
+#pragma unroll
+    for (int u = 0; u < kEmitUnroll; ++u) {
+      const uint32_t e = e0 + u * kWave + lane_id();
+      key[u] = e < t.total ? tile_entry(t, e, cand_row, cap).y & 0x7FFFFFFFu : 0u;
     }
-    const uint32_t prev = __shfl_up(bk, 1, kWave);
-    const bool leader = lane == 0 || bk != prev;
-    const uint64_t leaders = __ballot(leader);
-    const uint32_t incl = wave_inclusive_scan(val);       // a wave holds 64 entries: no carry
-    const uint64_t later = lane == kWave - 1 ? 0ull : leaders & ~((2ull << lane) - 1ull);
-    const int last = later ? __ffsll((unsigned long long)later) - 2 : kWave - 1;
-    const uint32_t run = __shfl(incl, last, kWave) - (incl - val);
-    if (leader && bk != 0xFFFFFFFFu) atomicAdd(&bc[bk], run);
-  }
-}
-
-// Sum of the 256 bucket counters of each super-bucket (one block each), unpacked to 64 bits.
-__global__ __launch_bounds__(kBlock) void k_super_sums(const uint32_t* __restrict__ bucket_cnt,
-                                                       uint32_t nbk,
-                                                       unsigned long long* __restrict__ super_cnt,
-                                                       uint32_t nsup,
-                                                       const uint32_t* __restrict__ need) {
-  static_assert((1u << kSuperShift) == kBlock, "one bucket per thread");
-  __shared__ unsigned long long lds[kBlock / kWave];
-  const uint32_t row = blockIdx.y;
-  if (need[row]) return;
-  const uint32_t bk = blockIdx.x * kBlock + threadIdx.x;
-  const uint32_t c = bk < nbk ? bucket_cnt[(uint64_t)row * nbk + bk] : 0u;
-  unsigned long long v = ((unsigned long long)(c >> 16) << 32) | (c & 0xFFFFu);
 #pragma unroll
-  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  if (lane_id() == 0) lds[threadIdx.x / kWave] = v;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long t = 0;
-    for (int i = 0; i < kBlock / kWave; ++i) t += lds[i];
-    super_cnt[(uint64_t)row * nsup + blockIdx.x] = t;
+    for (int u = 0; u < kEmitUnroll; ++u) {
+      const uint32_t e = e0 + u * kWave + lane_id();
+      gt += (e < t.total && key[u] > T) ? 1u : 0u;
+      eq += (e < t.total && key[u] == T) ? 1u : 0u;
+    }
   }
+  gt = wave_sum(gt);
+  eq = wave_sum(eq);
+  if (lane_id() == 0)
+    tile_cnt[(uint64_t)row * ntiles + tile] = ((unsigned long long)eq << 32) | gt;
 }
 
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
-#pragma unroll
-  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
-}
-
-// One wave per group of GROUP consecutive buckets (GROUP = 1, 8 or 64, chosen so that the
-// launch has enough waves; a group never straddles a super-bucket).  The first GROUP lanes
-// fetch the group's counters; a wave with a non-empty bucket adds up the super-buckets and
-// buckets before its group (its place in the message), then walks its non-empty buckets;
-// inside a bucket lane l owns words 2l and 2l+1 of both bitmaps.
-template <int GROUP>
-__global__ __launch_bounds__(kBlock) void k_emit_bitmap(
-    float* __restrict__ x, uint64_t d, uint32_t K, const FastSel* __restrict__ sel,
-    uint32_t* __restrict__ bm_gt, uint32_t* __restrict__ bm_eq, uint64_t words_per_row,
-    const uint32_t* __restrict__ bucket_cnt, uint32_t nbk,
-    const unsigned long long* __restrict__ super_cnt, uint32_t nsup,
-    const uint32_t* __restrict__ need, uint32_t* __restrict__ out_idx,
-    float* __restrict__ out_val) {
-  const uint32_t row = blockIdx.y;
+// One block per row; every thread owns a contiguous share of the tiles.
+__global__ __launch_bounds__(kBlock) void k_dir_scan(unsigned long long* __restrict__ tile_cnt,
+                                                     uint32_t ntiles,
+                                                     const uint32_t* __restrict__ need) {
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  const uint32_t row = blockIdx.x;
   if (need[row]) return;
-  const uint32_t group = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  const uint32_t first = group * GROUP;                      // first bucket of the group
-  const uint32_t bk_mine = first + lane_id();
-  const uint32_t* bc = bucket_cnt + (uint64_t)row * nbk;
-  const uint32_t my_cnt = (lane_id() < GROUP && bk_mine < nbk) ? bc[bk_mine] : 0u;
-  uint64_t live = __ballot(my_cnt != 0);
-  if (live == 0) return;
-  const uint32_t r = sel[row].r;
-  // counts before the group: whole super-buckets, then the buckets of this super-bucket
-  const uint32_t sup = first >> kSuperShift;
-  const unsigned long long* sc = super_cnt + (uint64_t)row * nsup;
-  unsigned long long before = 0;
-  for (uint32_t s = lane_id(); s < sup; s += kWave) before += sc[s];
-  for (uint32_t b = (sup << kSuperShift) + lane_id(); b < first; b += kWave) {
-    const uint32_t c = bc[b];
-    before += ((unsigned long long)(c >> 16) << 32) | (c & 0xFFFFu);
+  unsigned long long* tc = tile_cnt + (uint64_t)row * ntiles;
+  const uint32_t per = (ntiles + kBlock - 1) / kBlock;
+  const uint32_t lo = min(threadIdx.x * per, ntiles), hi = min(lo + per, ntiles);
+  uint32_t gt = 0, eq = 0;
+  for (uint32_t i = lo; i < hi; ++i) {
+    const unsigned long long v = tc[i];
+    gt += (uint32_t)v;
+    eq += (uint32_t)(v >> 32);
   }
-  before = wave_sum_u64(before);
-  // exclusive prefix over the buckets of the group (packed: equal << 16 | greater; a group
-  // holds at most 64 * 4096 coordinates, so sum the halves separately)
-  const uint32_t incl_gt = wave_inclusive_scan(my_cnt & 0xFFFFu);
-  const uint32_t incl_eq = wave_inclusive_scan(my_cnt >> 16);
-  const uint32_t my_gt0 = (uint32_t)(before & 0xFFFFFFFFull) + incl_gt - (my_cnt & 0xFFFFu);
-  const uint32_t my_eq0 = (uint32_t)(before >> 32) + incl_eq - (my_cnt >> 16);
-  uint32_t* wg = bm_gt + (uint64_t)row * words_per_row;
-  uint32_t* we = bm_eq + (uint64_t)row * words_per_row;
+  uint32_t total;
+  uint32_t run_gt = block_exclusive_scan(gt, lds, &total);
+  uint32_t run_eq = block_exclusive_scan(eq, lds, &total);
+  for (uint32_t i = lo; i < hi; ++i) {
+    const unsigned long long v = tc[i];
+    tc[i] = ((unsigned long long)run_eq << 32) | run_gt;
+    run_gt += (uint32_t)v;
+    run_eq += (uint32_t)(v >> 32);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_dir_emit(
+    uint2* __restrict__ dir, uint32_t nwc_pad, const uint2* __restrict__ cand, uint32_t cap,
+    const FastSel* __restrict__ sel, const uint32_t* __restrict__ need,
+    const unsigned long long* __restrict__ tile_cnt, uint32_t ntiles, float* __restrict__ x,
+    uint64_t d, uint32_t K, uint32_t* __restrict__ out_idx, float* __restrict__ out_val) {
+  __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
+  const uint32_t row = blockIdx.y;
+  const uint32_t w = threadIdx.x / kWave;
+  const uint32_t tile = blockIdx.x * kWavesPerBlock + w;
+  if (tile >= ntiles) return;
+  uint2* dir_row = dir + (uint64_t)row * nwc_pad;
+  uint32_t mine;
+  const TileView t = load_tile(dir_row, tile, s_off[w], s_start[w], &mine);
+  if (mine) dir_row[(uint64_t)tile * kTileChunks + lane_id()] = make_uint2(0u, 0u);
+  if (need[row] || t.total == 0) return;
+  const FastSel s = sel[row];
+  const unsigned long long before = tile_cnt[(uint64_t)row * ntiles + tile];
+  uint32_t run_gt = (uint32_t)before, run_eq = (uint32_t)(before >> 32);
+  const uint2* cand_row = cand + (uint64_t)row * kSubLists * cap;
   float* xr = x + (uint64_t)row * d;
   uint32_t* oi = out_idx + (uint64_t)row * K;
   float* ov = out_val + (uint64_t)row * K;
-  // the group's slice of the message
-  const uint32_t grp_gt0 = __shfl(my_gt0, 0, kWave), grp_eq0 = __shfl(my_eq0, 0, kWave);
-  const uint32_t grp_gt1 = grp_gt0 + __shfl(incl_gt, kWave - 1, kWave);
-  const uint32_t grp_eq1 = grp_eq0 + __shfl(incl_eq, kWave - 1, kWave);
-  const uint32_t p_first = grp_gt0 + min(grp_eq0, r);
-  const uint32_t p_end = min(grp_gt1 + min(grp_eq1, r), K);
-  // Part one writes the indices only.  The words of up to kBatch buckets are fetched before
-  // any of them is walked, so a wave waits for memory once per batch, not once per bucket.
-  constexpr int kBatch = GROUP < 8 ? GROUP : 8;
-  while (live) {
-    int src[kBatch];
+  const uint64_t below = lanes_below();
+  for (uint32_t e0 = 0; e0 < t.total; e0 += kWave * kEmitUnroll) {
+    uint2 en[kEmitUnroll];
 #pragma unroll
-    for (int b = 0; b < kBatch; ++b) {
-      src[b] = live ? __ffsll((unsigned long long)live) - 1 : -1;
-      live &= live - 1;
-    }
-    uint32_t g0[kBatch], g1[kBatch], e0[kBatch], e1[kBatch];
-#pragma unroll
-    for (int b = 0; b < kBatch; ++b) {
-      g0[b] = g1[b] = e0[b] = e1[b] = 0;
-      if (src[b] < 0) continue;
-      const uint32_t cnt = __shfl(my_cnt, src[b], kWave);
-      const uint64_t w0 = (uint64_t)(first + src[b]) * kBucketWords + 2u * lane_id();
-      if (cnt & 0xFFFFu) {
-        if (w0 < words_per_row) g0[b] = wg[w0];
-        if (w0 + 1 < words_per_row) g1[b] = wg[w0 + 1];
-      }
-      if (cnt >> 16) {
-        if (w0 < words_per_row) e0[b] = we[w0];
-        if (w0 + 1 < words_per_row) e1[b] = we[w0 + 1];
-      }
+    for (int u = 0; u < kEmitUnroll; ++u) {
+      const uint32_t e = e0 + u * kWave + lane_id();
+      en[u] = e < t.total ? tile_entry(t, e, cand_row, cap) : make_uint2(0u, 0u);
     }
 #pragma unroll
-    for (int b = 0; b < kBatch; ++b) {
-      if (src[b] < 0) continue;
-      const uint64_t w0 = (uint64_t)(first + src[b]) * kBucketWords + 2u * lane_id();
-      // per lane at most 64 bits of each kind: the packed scan cannot carry across halves
-      const uint32_t mine =
-          (__popc(g0[b]) + __popc(g1[b])) | ((__popc(e0[b]) + __popc(e1[b])) << 16);
-      const uint32_t pre = wave_inclusive_scan(mine) - mine;
-      uint32_t n_gt = __shfl(my_gt0, src[b], kWave) + (pre & 0xFFFFu);   // greater before me
-      uint32_t n_eq = __shfl(my_eq0, src[b], kWave) + (pre >> 16);       // equal before me
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const uint32_t gb = half == 0 ? g0[b] : g1[b], eb = half == 0 ? e0[b] : e1[b];
-        uint32_t bits = gb | eb;
-        const uint32_t base = (uint32_t)((w0 + half) * 32u);
-        while (bits) {
-          const uint32_t t = __ffs(bits) - 1;
-          bits &= bits - 1;
-          const bool is_gt = (gb >> t) & 1u;
-          if (is_gt || n_eq < r) {
-            const uint32_t pos = n_gt + min(n_eq, r);
-            if (pos < K) oi[pos] = base + t;
-          }
-          n_gt += is_gt ? 1u : 0u;
-          n_eq += is_gt ? 0u : 1u;
+    for (int u = 0; u < kEmitUnroll; ++u) {
+      const uint32_t e = e0 + u * kWave + lane_id();
+      const uint32_t key = en[u].y & 0x7FFFFFFFu;
+      const bool is_gt = e < t.total && key > s.T;
+      const bool is_eq = e < t.total && key == s.T;
+      const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+      const uint32_t n_gt = run_gt + __popcll(m_gt & below);       // greater before me
+      const uint32_t n_eq = run_eq + __popcll(m_eq & below);       // equal before me
+      if (is_gt || (is_eq && n_eq < s.r)) {
+        const uint32_t pos = n_gt + min(n_eq, s.r);
+        const uint32_t idx = en[u].x;
+        if (pos < K && idx < d) {
+          oi[pos] = idx;
+          ov[pos] = __uint_as_float(en[u].y);
+          xr[idx] = 0.0f;
         }
       }
-      if (g0[b]) wg[w0] = 0;
-      if (g1[b]) wg[w0 + 1] = 0;
-      if (e0[b]) we[w0] = 0;
-      if (e1[b]) we[w0 + 1] = 0;
-    }
-  }
-  // Part two: the values, one lane per entry of the group's slice.  The indices were stored
-  // by this wave; the workgroup-scope fence orders those stores before the loads.
-  __threadfence_block();
-  for (uint32_t p = p_first + lane_id(); p < p_end; p += kWave) {
-    const uint32_t idx = oi[p];
-    if (idx < d) {
-      ov[p] = xr[idx];
-      xr[idx] = 0.0f;
+      run_gt += __popcll(m_gt);
+      run_eq += __popcll(m_eq);
     }
   }
 }
@@ -594,9 +567,8 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.stride = (uint32_t)stride;
   p.target = (uint32_t)target;
   p.cap = (uint32_t)cap;
-  p.nbk = (uint32_t)((d + 4095) / 4096);
-  p.nsup = (p.nbk + (1u << kSuperShift) - 1) >> kSuperShift;
-  p.words_per_row = (d + 31) / 32;
+  p.ntiles = (uint32_t)(((d + kWaveChunk - 1) / kWaveChunk + 1 + kTileChunks - 1) / kTileChunks);
+  p.nwc_pad = p.ntiles * kTileChunks;
   return p;
 }
 
@@ -606,10 +578,10 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   const dim3 block(kBlock);
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
   const dim3 dense_grid((nwc + kStreamWaves - 1) / kStreamWaves, rows);
-  unsigned long long* super_cnt = reinterpret_cast<unsigned long long*>(sc.super_cnt);
-  if (*sc.dirty) {       // an earlier call failed between marking and emission: clear the bits
-    hipError_t e = fill_u32(s, sc.bitmap_gt, (uint64_t)sc.rows * pl.words_per_row, 0);
-    if (e == hipSuccess) e = fill_u32(s, sc.bitmap_eq, (uint64_t)sc.rows * pl.words_per_row, 0);
+  unsigned long long* tile_cnt = reinterpret_cast<unsigned long long*>(sc.tile_cnt);
+  if (*sc.dirty) {       // an earlier call failed before its emission: clear what it left
+    hipError_t e = fill_u32(s, reinterpret_cast<uint32_t*>(sc.dir),
+                            (uint64_t)sc.rows * pl.nwc_pad * 2, 0);
     if (e == hipSuccess) e = fill_u32(s, sc.sample_hist, (uint64_t)sc.rows * kSampleBins, 0);
     if (e != hipSuccess) return e;
   }
@@ -620,22 +592,23 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   if (sample_blocks > 64) sample_blocks = 64;
   if (sample_blocks < 1) sample_blocks = 1;
   if (g != nullptr)
-    k_sample_hist<true><<<dim3(sample_blocks, rows), block, 0, s>>>(
-        g, x, d, alpha, pl.stride, sc.sample_hist, sc.bucket_cnt, pl.nbk);
+    k_sample_hist<true><<<dim3(sample_blocks, rows), block, 0, s>>>(g, x, d, alpha, pl.stride,
+                                                                    sc.sample_hist);
   else
-    k_sample_hist<false><<<dim3(sample_blocks, rows), block, 0, s>>>(
-        nullptr, x, d, 0.0f, pl.stride, sc.sample_hist, sc.bucket_cnt, pl.nbk);
+    k_sample_hist<false><<<dim3(sample_blocks, rows), block, 0, s>>>(nullptr, x, d, 0.0f,
+                                                                     pl.stride, sc.sample_hist);
   BTS_LAUNCH_CHECK();
   k_pick_bound<<<dim3(rows), block, 0, s>>>(sc.sample_hist, pl.target, sc.lower_key, sc.cand_cnt);
   BTS_LAUNCH_CHECK();
-  // 2. the dense pass
+  // 2. the dense pass (a wave of the grid may lie past the row's last chunk, never past
+  // the padded directory)
   if (ev0) (void)hipEventRecord(ev0, s);
   if (g != nullptr)
     k_stream_capture<true><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
-        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap);
+        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad);
   else
     k_stream_capture<false><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
-        nullptr, x, d, 0.0f, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap);
+        nullptr, x, d, 0.0f, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad);
   BTS_LAUNCH_CHECK();
   if (ev1) (void)hipEventRecord(ev1, s);
   // 3 + 4. verify and select: a few blocks per row, each taking whole lists (about 4096
@@ -656,32 +629,14 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   BTS_CAND_PASS(2)
 #undef BTS_CAND_PASS
   // 5. emit
-  uint32_t parts = (pl.cap + 2047) / 2048;            // blocks per list
-  if (parts > 4) parts = 4;
-  if (parts < 1) parts = 1;
-  k_mark<<<dim3(kSubLists * parts, rows), block, 0, s>>>(
-      sc.cand, sc.cand_cnt, pl.cap, sel, sc.need, sc.bitmap_gt, sc.bitmap_eq, pl.words_per_row,
-      sc.bucket_cnt, pl.nbk);
+  const dim3 tgrid((pl.ntiles + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  k_dir_count<<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                      tile_cnt, pl.ntiles);
   BTS_LAUNCH_CHECK();
-  k_super_sums<<<dim3(pl.nsup, rows), block, 0, s>>>(sc.bucket_cnt, pl.nbk, super_cnt, pl.nsup,
-                                                     sc.need);
+  k_dir_scan<<<dim3(rows), block, 0, s>>>(tile_cnt, pl.ntiles, sc.need);
   BTS_LAUNCH_CHECK();
-  // enough waves to fill the chip, few enough that empty groups stay cheap
-  const uint64_t buckets = (uint64_t)rows * pl.nbk;
-  const int group = buckets >= (64ull << 16) ? 64 : (buckets >= (8ull << 14) ? 8 : 1);
-  const uint32_t groups = (pl.nbk + group - 1) / group;
-  const dim3 egrid((groups + kWavesPerBlock - 1) / kWavesPerBlock, rows);
-#define BTS_EMIT(G)                                                                          \
-  k_emit_bitmap<G><<<egrid, block, 0, s>>>(x, d, K, sel, sc.bitmap_gt, sc.bitmap_eq,          \
-                                           pl.words_per_row, sc.bucket_cnt, pl.nbk, super_cnt, \
-                                           pl.nsup, sc.need, out_idx, out_val)
-  if (group == 64)
-    BTS_EMIT(64);
-  else if (group == 8)
-    BTS_EMIT(8);
-  else
-    BTS_EMIT(1);
-#undef BTS_EMIT
+  k_dir_emit<<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need, tile_cnt,
+                                     pl.ntiles, x, d, K, out_idx, out_val);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   return hipSuccess;

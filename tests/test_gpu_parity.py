@@ -373,7 +373,7 @@ def test_resume_from_copied_state_and_path_switching(G, oracle):
     """The state of the algorithm lives in the caller's buffers only: four steps in one go
     equal two steps, a copy of (eps, delta, w) into new buffers and a NEW context, and two
     more steps.  The first run also switches the select path every step, which checks that
-    each path leaves the shared scratch (bitmaps, counters, histograms) clean."""
+    each path leaves the shared scratch (directory, counters, histograms) clean."""
     import paper_2209_15203_amd as bts
     cfg = wl.CONFIGS["C3"].scaled(300_007, N=6, steps=4)
     D = G.dev()
