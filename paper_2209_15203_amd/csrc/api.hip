@@ -25,6 +25,7 @@ struct bts_ctx {
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
   uint32_t* agg_offsets;        // their exclusive scan (unidirectional message placement)
   uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
+  uint32_t* agg_any;            // per-range "somebody names it" flags, used with the tables
   bool agg_tables_bad;          // a launch failed while the tables were in use: stop using them
   DiagScratch diag;             // allocated by bts_enable_diagnostics only
   bool diag_ready;
@@ -47,8 +48,16 @@ int fail_hip(bts_ctx* ctx, hipError_t e) {
   return BTS_EHIP;
 }
 
-uint32_t* tab_start(const bts_ctx* ctx) { return ctx->agg_tables_bad ? nullptr : ctx->agg_start; }
-uint32_t* tab_end(const bts_ctx* ctx) { return ctx->agg_tables_bad ? nullptr : ctx->agg_end; }
+AggScratch agg_scratch(const bts_ctx* ctx) {
+  AggScratch a;
+  a.cnt = ctx->agg_ranges;
+  a.off = ctx->agg_offsets;
+  const bool tables = !ctx->agg_tables_bad && ctx->agg_start != nullptr;
+  a.tab_start = tables ? ctx->agg_start : nullptr;
+  a.tab_end = tables ? ctx->agg_end : nullptr;
+  a.any = tables ? ctx->agg_any : nullptr;
+  return a;
+}
 
 // Zero-filled device allocation owned by the context.
 template <typename T>
@@ -86,7 +95,8 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
 bool alloc_agg_tables(bts_ctx* ctx) {
   const size_t words = (size_t)aggregate_ranges(ctx->d) * (size_t)ctx->N;
   if (ctx->K_up == 0 || words * 8 > (256ull << 20)) return true;
-  return dev_alloc(ctx, &ctx->agg_start, words) && dev_alloc(ctx, &ctx->agg_end, words);
+  return dev_alloc(ctx, &ctx->agg_start, words) && dev_alloc(ctx, &ctx->agg_end, words) &&
+         dev_alloc(ctx, &ctx->agg_any, (size_t)aggregate_ranges(ctx->d));
 }
 
 void release(bts_ctx* ctx) {
@@ -178,7 +188,7 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->diag = DiagScratch{};
   ctx->diag_ready = false;
   ctx->agg_offsets = nullptr;
-  ctx->agg_start = ctx->agg_end = nullptr;
+  ctx->agg_start = ctx->agg_end = ctx->agg_any = nullptr;
   ctx->agg_tables_bad = false;
   if (hipGetDevice(&ctx->device) != hipSuccess) {
     delete ctx;
@@ -196,8 +206,8 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
             dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
             dev_alloc(ctx, &ctx->dense.tile_sums, (size_t)rows * 2 * dense_scan_tiles(nwc)) &&
-            dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_ranges(d)) &&
-            dev_alloc(ctx, &ctx->agg_offsets, (size_t)aggregate_ranges(d)) &&
+            dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_scratch_words(d)) &&
+            dev_alloc(ctx, &ctx->agg_offsets, (size_t)aggregate_scratch_words(d)) &&
             alloc_agg_tables(ctx);
   if (!ok) {
     (void)hipGetLastError();
@@ -246,7 +256,7 @@ int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, 
   if (!ctx || !p || !delta) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
   hipError_t e = aggregate(ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, delta,
-                           ctx->d, union_nnz, ctx->agg_ranges, tab_start(ctx), tab_end(ctx));
+                           ctx->d, union_nnz, agg_scratch(ctx));
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -292,7 +302,7 @@ int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float*
   if (rc != BTS_OK) return rc;
   hipError_t e = aggregate_update_unidirectional(
       ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, w, ctx->d, alpha_out, dn_idx,
-      dn_val, dn_count, ctx->agg_ranges, ctx->agg_offsets, tab_start(ctx), tab_end(ctx));
+      dn_val, dn_count, agg_scratch(ctx));
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -331,7 +341,7 @@ int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, floa
   if (rc != BTS_OK) return rc;
   e = diag_after_step(ctx->stream, ctx->diag, ctx->dense, eps, delta, p, (uint32_t)ctx->N, ctx->d,
                       ctx->K_up, ctx->K_dn, alpha_in, up_idx, up_val, dn_idx, dn_val,
-                      ctx->agg_ranges, ctx->agg_offsets, tab_start(ctx), tab_end(ctx), diag);
+                      agg_scratch(ctx), diag);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 

@@ -97,23 +97,26 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1);
 
 // ---- server side ------------------------------------------------------------------------
-// range_scratch: aggregate_ranges(d) words, used only when union_nnz is wanted.
-// tab_start/tab_end: optional aggregate_ranges(d) x N tables (all zero between calls) that
-// replace the per-range binary searches; null = search.
 uint32_t aggregate_ranges(uint64_t d);
+uint32_t aggregate_scratch_words(uint64_t d);
+struct AggScratch {
+  uint32_t* cnt;        // aggregate_scratch_words(d): per-range counts or per-wave partial sums
+  uint32_t* off;        // aggregate_scratch_words(d): exclusive scan of the per-range counts
+  uint32_t* tab_start;  // optional aggregate_ranges(d) x N tables (all zero between calls) that
+  uint32_t* tab_end;    //   replace the per-range binary searches; null = search
+  uint32_t* any;        // aggregate_ranges(d) flags (all zero between calls), used with the tables
+};
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
-                     uint32_t* range_scratch, uint32_t* tab_start, uint32_t* tab_end);
+                     const AggScratch& sc);
 // Algorithm 1's server and update in one: w -= alpha_out * sum_q p_q Top_K(a^q), the sum
 // also returned as a sparse message (named coordinates ascending; msg_idx/msg_val nullable,
-// room for N*K_up pairs; msg_count nullable).  range_cnt/range_off: aggregate_ranges(d)
-// words each.
+// room for N*K_up pairs; msg_count nullable).
 hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx,
                                            const float* up_val, const float* p, uint32_t N,
                                            uint32_t K_up, float* w, uint64_t d, float alpha_out,
                                            uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
-                                           uint32_t* range_cnt, uint32_t* range_off,
-                                           uint32_t* tab_start, uint32_t* tab_end);
+                                           const AggScratch& sc);
 // ---- per-step diagnostics (rho, rho_hat, 1 - gamma, nnz fraction) -------------------------
 struct DiagScratch {
   float* u;          // d: sum_q p_q a^q
@@ -135,8 +138,7 @@ hipError_t diag_after_step(hipStream_t s, const DiagScratch& ds, const DenseScra
                            const float* eps, const float* delta, const float* p, uint32_t N,
                            uint64_t d, uint32_t K_up, uint32_t K_dn, float alpha,
                            const uint32_t* up_idx, const float* up_val, const uint32_t* dn_idx,
-                           const float* dn_val, uint32_t* agg_cnt, uint32_t* agg_off,
-                           uint32_t* tab_start, uint32_t* tab_end, double* diag);
+                           const float* dn_val, const AggScratch& agg, double* diag);
 
 hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint32_t K,
                       float alpha_out, float* w, uint64_t d);

@@ -235,8 +235,7 @@ hipError_t diag_after_step(hipStream_t s, const DiagScratch& ds, const DenseScra
                            const float* eps, const float* delta, const float* p, uint32_t N,
                            uint64_t d, uint32_t K_up, uint32_t K_dn, float alpha,
                            const uint32_t* up_idx, const float* up_val, const uint32_t* dn_idx,
-                           const float* dn_val, uint32_t* agg_cnt, uint32_t* agg_off,
-                           uint32_t* tab_start, uint32_t* tab_end, double* diag) {
+                           const float* dn_val, const AggScratch& agg, double* diag) {
   double* part = ds.part;
   double* p_rho = part + kParts;
   double* p_hat = part + 2 * kParts;
@@ -253,7 +252,7 @@ hipError_t diag_after_step(hipStream_t s, const DiagScratch& ds, const DenseScra
   if (e != hipSuccess) return e;
   // m = sum_q p_q Top_K(a^q), sparse
   e = aggregate_update_unidirectional(s, up_idx, up_val, p, N, K_up, nullptr, d, 0.0f, ds.m_idx,
-                                      ds.m_val, ds.m_cnt, agg_cnt, agg_off, tab_start, tab_end);
+                                      ds.m_val, ds.m_cnt, agg);
   if (e != hipSuccess) return e;
   k_sparse_dist2<<<dim3(kParts), dim3(kBlock), 0, s>>>(ds.a_idx, ds.a_val, K_dn, dn_idx, dn_val,
                                                        K_dn, nullptr, p_rho);

@@ -3,13 +3,14 @@
 // and the model update  w_t = w_{t-1} - Top_K(g_t)  on the received pairs.
 //
 // Aggregation is deterministic without float atomics: the coordinate axis is cut into
-// ranges of kAggWidth coordinates, one workgroup owns a range, and inside it the workers
-// are applied one after the other in ascending q (a worker never names a coordinate twice,
-// so the pairs of one worker are applied in parallel; a workgroup barrier separates
-// consecutive workers).  Each worker's pairs that fall into the range are found by binary
-// search in its sorted index list.  The range's pairs are staged in LDS and the touched
-// part of delta is gathered into an LDS accumulator first, so that the N dependent
-// rounds run at LDS latency instead of HBM latency.
+// ranges of kAggWidth coordinates and ONE WAVE owns a range.  It stages the range's pairs
+// in (worker, index) order in its part of LDS, gathers the touched part of delta into an
+// LDS accumulator, and applies the workers one after the other in ascending q (a worker
+// never names a coordinate twice, so the pairs of one worker are applied in parallel).
+// Consecutive workers are ordered by the wave's program order alone: no workgroup barrier
+// and no HBM latency inside the N dependent rounds.  Where each worker's sorted list enters
+// and leaves each range comes from a table (or from binary searches when the table would be
+// too large), and a flag per range lets a wave skip, 64 at a time, the ranges nobody names.
 
 #include "bts_device.h"
 
@@ -18,9 +19,10 @@ namespace bts {
 namespace {
 
 constexpr int kAggBlock = 256;
-constexpr int kAggTile = 256;          // workers whose range bounds are held in LDS at a time
-constexpr uint32_t kAggWidth = 4096;   // coordinates per range
-constexpr uint32_t kAggStage = 1024;   // pairs staged in LDS at a time
+constexpr int kAggWaves = kAggBlock / kWave;
+constexpr uint32_t kAggWidth = 1024;   // coordinates per range
+constexpr uint32_t kAggStage = 256;    // pairs a wave stages in LDS at a time
+constexpr uint32_t kAggMaxBlocks = 2048;
 
 __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__ a, uint32_t n,
                                                     uint32_t key) {
@@ -34,18 +36,50 @@ __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__
 
 // Where each worker's sorted index list enters and leaves each range: pair j of worker q
 // opens range r if its predecessor lies in another range and closes it if its successor
-// does.  The table is all zero between calls (the aggregation clears what it reads).
+// does; the opener also raises the range's flag.  Table and flags are all zero between
+// calls (the aggregation clears what it reads).
 __global__ void k_range_bounds(const uint32_t* __restrict__ up_idx, uint32_t N, uint32_t K_up,
                                uint64_t d, uint32_t* __restrict__ start,
-                               uint32_t* __restrict__ end) {
+                               uint32_t* __restrict__ end, uint32_t* __restrict__ any) {
   const uint32_t q = blockIdx.y;
   const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= K_up) return;
   const uint32_t* row = up_idx + (uint64_t)q * K_up;
   if (row[j] >= d) return;                       // invalid input never reaches the table
   const uint32_t r = row[j] / kAggWidth;
-  if (j == 0 || row[j - 1] / kAggWidth != r) start[(uint64_t)r * N + q] = j;
+  if (j == 0 || row[j - 1] / kAggWidth != r) {
+    start[(uint64_t)r * N + q] = j;
+    any[r] = 1u;
+  }
   if (j + 1 == K_up || row[j + 1] / kAggWidth != r) end[(uint64_t)r * N + q] = j + 1;
+}
+
+constexpr uint32_t kAggNoRel = 0xFFFFu;
+
+struct AggWaveLds {
+  float acc[kAggWidth];                 // g_t of the touched coordinates
+  uint32_t touched[kAggWidth / 32];
+  uint32_t seen[kAggWidth / 4];         // per coordinate, one byte: pairs of the stage so far
+  uint32_t lo[kWave];                   // per worker of the tile: first pair in the range
+  uint32_t pref[kWave + 1];             // pairs of the tile's earlier workers in the range
+  float p[kWave];
+  uint32_t lvl_off[kWave + 1];          // first slot of each depth level in order[]
+  uint32_t lvl_fill[kWave];
+  uint32_t e_key[kAggStage];            // coordinate - c0 (low 16 bits) | worker in the tile << 16
+  float e_val[kAggStage];
+  uint16_t order[kAggStage];            // the stage's pairs grouped by depth level
+};
+
+// Orders this wave's LDS accesses across its lanes (the hardware runs a wave's LDS
+// instructions in order; this keeps the compiler from moving them).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint32_t seen_byte(const AggWaveLds& L, uint32_t rel) {
+  return (L.seen[rel >> 2] >> (8 * (rel & 3))) & 0xFFu;
 }
 
 // MODE 0: bidirectional server (Algorithm 2): delta[i] = delta[i] + sum_q p_q v_q[i].
@@ -53,31 +87,33 @@ __global__ void k_range_bounds(const uint32_t* __restrict__ up_idx, uint32_t N, 
 // MODE 2: unidirectional server and update (Algorithm 1): g_t[i] = sum_q p_q v_q[i] from +0,
 //         the named coordinates and their g_t written in ascending order to the message at
 //         range_off[range] + rank, and w[i] = fma(-alpha_out, g_t[i], w[i]).
+// Returns the number of distinct coordinates named in range r (same value in every lane).
+//
+// The pairs of the range are staged in (worker, index) order, kAggStage at a time (at most
+// 64 workers per tile).  The depth of a pair is the number of earlier pairs of the stage on
+// the same coordinate; pairs of one depth name distinct coordinates, so they are applied in
+// parallel, and going through the depths in ascending order applies each coordinate's
+// pairs in ascending q.  Stages and tiles follow each other in ascending q as well.
 template <int MODE>
-__global__ __launch_bounds__(kAggBlock) void k_aggregate(
-    const uint32_t* __restrict__ up_idx, const float* __restrict__ up_val,
-    const float* __restrict__ p, uint32_t N, uint32_t K_up, float* __restrict__ dense,
-    uint64_t d, uint32_t* __restrict__ range_nnz, uint32_t* __restrict__ tab_start,
+__device__ __forceinline__ uint32_t aggregate_range(
+    AggWaveLds& L, uint32_t r, const uint32_t* __restrict__ up_idx,
+    const float* __restrict__ up_val, const float* __restrict__ p, uint32_t N, uint32_t K_up,
+    float* __restrict__ dense, uint64_t d, uint32_t* __restrict__ tab_start,
     uint32_t* __restrict__ tab_end, const uint32_t* __restrict__ range_off, float neg_alpha,
     uint32_t* __restrict__ msg_idx, float* __restrict__ msg_val) {
-  __shared__ float acc[kAggWidth];                  // g_t of the touched coordinates
-  __shared__ uint32_t touched[kAggWidth / 32];
-  __shared__ uint32_t s_lo[kAggTile], s_pref[kAggTile + 1];
-  __shared__ float s_p[kAggTile];
-  __shared__ uint32_t e_rel[kAggStage];
-  __shared__ float e_val[kAggStage];
-  __shared__ uint32_t lds[kAggBlock / kWave + 1];
-  const uint64_t c0 = (uint64_t)blockIdx.x * kAggWidth;
+  const uint32_t lane = lane_id();
+  const uint64_t c0 = (uint64_t)r * kAggWidth;
   const uint64_t c1 = min(c0 + (uint64_t)kAggWidth, d);
-  for (uint32_t i = threadIdx.x; i < kAggWidth / 32; i += kAggBlock) touched[i] = 0;
+  if (lane < kAggWidth / 32) L.touched[lane] = 0;
+  wave_lds_sync();
   uint32_t fresh = 0;
-  for (uint32_t q0 = 0; q0 < N; q0 += kAggTile) {
-    const uint32_t nq = min((uint32_t)kAggTile, N - q0);
+  for (uint32_t q0 = 0; q0 < N; q0 += kWave) {
+    const uint32_t nq = min((uint32_t)kWave, N - q0);
     // where each worker of the tile enters and leaves the range
     uint32_t lo = 0, n = 0;
-    if (threadIdx.x < nq) {
+    if (lane < nq) {
       if (tab_start != nullptr) {
-        const uint64_t at = (uint64_t)blockIdx.x * N + q0 + threadIdx.x;
+        const uint64_t at = (uint64_t)r * N + q0 + lane;
         lo = tab_start[at];
         const uint32_t hi = tab_end[at];
         n = (hi > lo && hi <= K_up) ? hi - lo : 0u;
@@ -86,89 +122,130 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
           tab_end[at] = 0;
         }
       } else {
-        const uint32_t* row = up_idx + (uint64_t)(q0 + threadIdx.x) * K_up;
+        const uint32_t* row = up_idx + (uint64_t)(q0 + lane) * K_up;
         lo = lower_bound_u32(row, K_up, (uint32_t)c0);
         n = lower_bound_u32(row, K_up, (uint32_t)c1) - lo;   // c1 <= d < 2^32
       }
-      s_p[threadIdx.x] = p[q0 + threadIdx.x];
+      L.p[lane] = p[q0 + lane];
     }
-    uint32_t total;
-    const uint32_t pref = block_exclusive_scan(n, lds, &total);   // barriers inside
-    s_lo[threadIdx.x] = lo;
-    s_pref[threadIdx.x] = pref;
-    if (threadIdx.x == kAggBlock - 1) s_pref[kAggTile] = total;
-    __syncthreads();
-    // the tile's pairs in (q, index) order, kAggStage at a time
-    uint32_t t_first = 0;                                   // first worker of the stage
+    const uint32_t incl = wave_inclusive_scan(n);
+    const uint32_t total = __shfl(incl, kWave - 1, kWave);
+    if (total == 0) continue;
+    L.lo[lane] = lo;
+    L.pref[lane] = incl - n;
+    if (lane == kWave - 1) L.pref[kWave] = total;
+    wave_lds_sync();
     for (uint32_t e0 = 0; e0 < total; e0 += kAggStage) {
-      const uint32_t e1 = min(e0 + kAggStage, total);
-      for (uint32_t e = e0 + threadIdx.x; e < e1; e += kAggBlock) {
-        // worker of pair e: the last t with s_pref[t] <= e
-        uint32_t a = 0, b = nq;
-        while (b - a > 1) {
-          const uint32_t m = (a + b) >> 1;
-          if (s_pref[m] <= e) a = m; else b = m;
-        }
-        const uint64_t src = (uint64_t)(q0 + a) * K_up + s_lo[a] + (e - s_pref[a]);
+      const uint32_t ne = min(kAggStage, total - e0);        // pairs in the stage
+      // 1. fetch the stage's pairs (independent loads)
+      for (uint32_t k = lane; k < ne; k += kWave) {
+        const uint32_t e = e0 + k;
+        uint32_t a = 0;                                      // the last worker with pref <= e
+#pragma unroll
+        for (uint32_t st = kWave / 2; st > 0; st >>= 1)
+          if (L.pref[a + st] <= e) a += st;
+        const uint64_t src = (uint64_t)(q0 + a) * K_up + L.lo[a] + (e - L.pref[a]);
         const uint32_t i = up_idx[src];
-        uint32_t rel = 0xFFFFFFFFu;
-        if (i >= c0 && i < c1) {                             // always true for sorted input
-          rel = i - (uint32_t)c0;
+        const uint32_t rel = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;   // always in
+        L.e_key[k] = rel | (a << 16);                                             // for sorted input
+        if (MODE != 1) L.e_val[k] = up_val[src];
+      }
+      if (MODE != 1 && lane < kWave) L.lvl_fill[lane] = 0;
+      wave_lds_sync();
+      // 2. first touches fetch the start value; depth of every pair
+      const uint32_t rounds = (ne + kWave - 1) / kWave;
+      for (uint32_t it = 0; it < rounds; ++it) {
+        const uint32_t k = it * kWave + lane;
+        const uint32_t rel = k < ne ? (L.e_key[k] & 0xFFFFu) : kAggNoRel;
+        const bool valid = rel != kAggNoRel;
+        uint32_t before = 0;
+        if (valid) {
           const uint32_t bit = 1u << (rel & 31);
-          const uint32_t old = atomicOr(&touched[rel >> 5], bit);
+          const uint32_t old = atomicOr(&L.touched[rel >> 5], bit);
           if (!(old & bit)) {                                // first touch: start value
-            if (MODE == 0) acc[rel] = dense[i];
-            if (MODE == 2) acc[rel] = 0.0f;
+            if (MODE == 0) L.acc[rel] = dense[c0 + rel];
+            if (MODE == 2) L.acc[rel] = 0.0f;
             ++fresh;
           }
+          if (MODE != 1) before = seen_byte(L, rel);
         }
         if (MODE != 1) {
-          e_rel[e - e0] = rel;
-          e_val[e - e0] = up_val[src];
+          wave_lds_sync();
+          if (valid) atomicAdd(&L.seen[rel >> 2], 1u << (8 * (rel & 3)));
+          wave_lds_sync();
+          const uint32_t here = valid ? seen_byte(L, rel) - before : 0u;   // of this round
+          uint64_t shared = __ballot(here > 1);              // lanes that share a coordinate
+          uint32_t rank = 0;
+          while (shared) {
+            const int j = __ffsll((unsigned long long)shared) - 1;
+            shared &= shared - 1;
+            const uint32_t rel_j = __shfl(rel, j, kWave);
+            if (valid && rel == rel_j && (uint32_t)j < lane) ++rank;
+          }
+          if (valid) {
+            // < 64 when no worker names a coordinate twice; clamped for lists that do
+            const uint32_t depth = min(before + rank, (uint32_t)kWave - 1);
+            L.e_key[k] |= depth << 24;                       // worker < 64 fits bits 16..23
+            atomicAdd(&L.lvl_fill[depth], 1u);
+          }
         }
       }
-      __syncthreads();
       if (MODE != 1) {
-        // one round per worker present in the stage, in ascending q
-        while (t_first + 1 < nq && s_pref[t_first + 1] <= e0) ++t_first;
-        for (uint32_t t = t_first; t < nq && s_pref[t] < e1; ++t) {
-          const uint32_t a = max(s_pref[t], e0), b = min(s_pref[t + 1], e1);
-          if (b <= a) continue;                              // uniform over the block
-          const float pq = s_p[t];
-          for (uint32_t e = a + threadIdx.x; e < b; e += kAggBlock) {
-            const uint32_t rel = e_rel[e - e0];
-            if (rel != 0xFFFFFFFFu) acc[rel] = __fmaf_rn(pq, e_val[e - e0], acc[rel]);
+        wave_lds_sync();
+        // 3. group the pairs by depth (the order inside a depth does not matter)
+        const uint32_t cnt = L.lvl_fill[lane];
+        const uint32_t cincl = wave_inclusive_scan(cnt);
+        const uint64_t used = __ballot(cnt != 0);
+        const uint32_t levels = used ? 64u - (uint32_t)__clzll((unsigned long long)used) : 0u;
+        wave_lds_sync();
+        L.lvl_off[lane] = cincl - cnt;
+        L.lvl_fill[lane] = cincl - cnt;
+        if (lane == kWave - 1) L.lvl_off[kWave] = cincl;
+        wave_lds_sync();
+        for (uint32_t k = lane; k < ne; k += kWave) {
+          const uint32_t key = L.e_key[k];
+          if ((key & 0xFFFFu) != kAggNoRel) {
+            L.order[atomicAdd(&L.lvl_fill[key >> 24], 1u)] = (uint16_t)k;
+            L.seen[(key & 0xFFFFu) >> 2] = 0;                // clean for the next stage
           }
-          __syncthreads();                                   // next worker may name the same i
+        }
+        wave_lds_sync();
+        // 4. apply, depth by depth
+        for (uint32_t l = 0; l < levels; ++l) {
+          const uint32_t b = L.lvl_off[l + 1];
+          for (uint32_t j = L.lvl_off[l] + lane; j < b; j += kWave) {
+            const uint32_t k = L.order[j];
+            const uint32_t key = L.e_key[k];
+            const uint32_t rel = key & 0xFFFFu;
+            L.acc[rel] = __fmaf_rn(L.p[(key >> 16) & 0xFFu], L.e_val[k], L.acc[rel]);
+          }
+          wave_lds_sync();                                   // the next depth may name the same i
         }
       }
     }
-    __syncthreads();
   }
   if (MODE == 0) {
-    // write the touched coordinates back
-    for (uint32_t w = threadIdx.x; w < kAggWidth / 32; w += kAggBlock) {
-      uint32_t bits = touched[w];
-      while (bits) {
-        const uint32_t t = __ffs(bits) - 1;
-        bits &= bits - 1;
-        const uint32_t rel = w * 32 + t;
-        dense[c0 + rel] = acc[rel];
-      }
+    // write the touched coordinates back: a lane takes half a bitmap word
+    static_assert(kAggWidth / 16 == kWave, "half a bitmap word per lane");
+    uint32_t bits = (L.touched[lane >> 1] >> (16 * (lane & 1))) & 0xFFFFu;
+    while (bits) {
+      const uint32_t t = __ffs(bits) - 1;
+      bits &= bits - 1;
+      const uint32_t rel = lane * 16 + t;
+      dense[c0 + rel] = L.acc[rel];
     }
   }
   if (MODE == 2) {
     // ordered message: rank of a coordinate = set bits below it in the range's bitmap
-    static_assert(kAggWidth / 32 <= kAggBlock, "one bitmap word per thread");
-    const uint32_t word = threadIdx.x < kAggWidth / 32 ? touched[threadIdx.x] : 0u;
-    uint32_t total;
-    uint32_t pos = range_off[blockIdx.x] + block_exclusive_scan(__popc(word), lds, &total);
+    const uint32_t word = lane < kAggWidth / 32 ? L.touched[lane] : 0u;
+    const uint32_t pc = __popc(word);
+    uint32_t pos = range_off[r] + wave_inclusive_scan(pc) - pc;
     uint32_t bits = word;
     while (bits) {
       const uint32_t t = __ffs(bits) - 1;
       bits &= bits - 1;
-      const uint32_t rel = threadIdx.x * 32 + t;
-      const float gt = acc[rel];
+      const uint32_t rel = lane * 32 + t;
+      const float gt = L.acc[rel];
       if (msg_idx != nullptr) {
         msg_idx[pos] = (uint32_t)c0 + rel;
         msg_val[pos] = gt;
@@ -177,11 +254,51 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
       ++pos;
     }
   }
-  if ((MODE == 0 || MODE == 1) && range_nnz != nullptr) {
-    uint32_t total;
-    (void)block_exclusive_scan(fresh, lds, &total);
-    if (threadIdx.x == 0) range_nnz[blockIdx.x] = total;
+  wave_lds_sync();
+  return wave_sum(fresh);
+}
+
+// Wave g of the grid takes the ranges g, g + W, g + 2W, ... (W = waves in the grid), so that
+// a cluster of busy ranges spreads over the whole chip; it reads the flags of 64 of its
+// ranges at a time and visits those that are raised.  any == nullptr: every range is visited.
+// MODE 0: nnz_out (nullable) gets one partial sum of distinct coordinates per wave.
+// MODE 1: nnz_out gets the count of every range.
+template <int MODE>
+__global__ __launch_bounds__(kAggBlock) void k_aggregate(
+    const uint32_t* __restrict__ up_idx, const float* __restrict__ up_val,
+    const float* __restrict__ p, uint32_t N, uint32_t K_up, float* __restrict__ dense,
+    uint64_t d, uint32_t ranges, uint32_t* __restrict__ nnz_out, uint32_t* __restrict__ tab_start,
+    uint32_t* __restrict__ tab_end, uint32_t* __restrict__ any,
+    const uint32_t* __restrict__ range_off, float neg_alpha, uint32_t* __restrict__ msg_idx,
+    float* __restrict__ msg_val) {
+  __shared__ AggWaveLds lds[kAggWaves];
+  AggWaveLds& L = lds[threadIdx.x / kWave];
+  const uint32_t lane = lane_id();
+  const uint32_t g = blockIdx.x * kAggWaves + threadIdx.x / kWave;
+  const uint32_t W = gridDim.x * kAggWaves;
+  for (uint32_t i = lane; i < kAggWidth / 4; i += kWave) L.seen[i] = 0;   // every stage cleans up
+  uint32_t nnz = 0;
+  for (uint64_t r0 = g; r0 < ranges; r0 += (uint64_t)W * kWave) {
+    const uint64_t mine = r0 + (uint64_t)lane * W;
+    bool live = mine < ranges;
+    if (live && any != nullptr) {
+      live = any[mine] != 0;
+      if (live && MODE != 1) any[mine] = 0;                  // leave the flags clear
+    }
+    if (MODE == 1 && mine < ranges && !live) nnz_out[mine] = 0;
+    uint64_t todo = __ballot(live);
+    while (todo) {
+      const uint32_t src = (uint32_t)__ffsll((unsigned long long)todo) - 1;
+      todo &= todo - 1;
+      const uint32_t r = (uint32_t)(r0 + (uint64_t)src * W);
+      const uint32_t cnt = aggregate_range<MODE>(L, r, up_idx, up_val, p, N, K_up, dense, d,
+                                                 tab_start, tab_end, range_off, neg_alpha,
+                                                 msg_idx, msg_val);
+      if (MODE == 1 && lane == 0) nnz_out[r] = cnt;
+      nnz += cnt;
+    }
   }
+  if (MODE == 0 && nnz_out != nullptr && lane == 0) nnz_out[g] = nnz;
 }
 
 // Exclusive scan of the per-range counts (one block); *total_out receives the sum.
@@ -227,26 +344,41 @@ __global__ void k_update(const uint32_t* __restrict__ idx, const float* __restri
 
 uint32_t aggregate_ranges(uint64_t d) { return (uint32_t)((d + kAggWidth - 1) / kAggWidth); }
 
+namespace {
+uint32_t agg_blocks(uint32_t ranges) {
+  uint32_t b = (ranges + kAggWaves - 1) / kAggWaves;
+  return b > kAggMaxBlocks ? kAggMaxBlocks : b;
+}
+}  // namespace
+
+uint32_t aggregate_scratch_words(uint64_t d) {
+  const uint32_t ranges = aggregate_ranges(d);
+  const uint32_t waves = agg_blocks(ranges) * kAggWaves;
+  return ranges > waves ? ranges : waves;
+}
+
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
-                     uint32_t* range_scratch, uint32_t* tab_start, uint32_t* tab_end) {
+                     const AggScratch& sc) {
   if (K_up == 0) {
     if (union_nnz != nullptr) return fill_u32(s, union_nnz, 1, 0);
     return hipSuccess;
   }
   const uint32_t ranges = aggregate_ranges(d);
-  if (tab_start != nullptr) {
-    k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(up_idx, N, K_up, d,
-                                                                    tab_start, tab_end);
+  const uint32_t blocks = agg_blocks(ranges);
+  uint32_t* any = sc.tab_start != nullptr ? sc.any : nullptr;
+  if (sc.tab_start != nullptr) {
+    k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(
+        up_idx, N, K_up, d, sc.tab_start, sc.tab_end, sc.any);
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
   }
-  k_aggregate<0><<<dim3(ranges), dim3(kAggBlock), 0, s>>>(
-      up_idx, up_val, p, N, K_up, delta, d, union_nnz != nullptr ? range_scratch : nullptr,
-      tab_start, tab_end, nullptr, 0.0f, nullptr, nullptr);
+  k_aggregate<0><<<dim3(blocks), dim3(kAggBlock), 0, s>>>(
+      up_idx, up_val, p, N, K_up, delta, d, ranges, union_nnz != nullptr ? sc.cnt : nullptr,
+      sc.tab_start, sc.tab_end, any, nullptr, 0.0f, nullptr, nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || union_nnz == nullptr) return e;
-  k_sum_ranges<<<dim3(1), dim3(1024), 0, s>>>(range_scratch, ranges, union_nnz);
+  k_sum_ranges<<<dim3(1), dim3(1024), 0, s>>>(sc.cnt, blocks * kAggWaves, union_nnz);
   return hipGetLastError();
 }
 
@@ -254,30 +386,31 @@ hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx
                                            const float* up_val, const float* p, uint32_t N,
                                            uint32_t K_up, float* w, uint64_t d, float alpha_out,
                                            uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
-                                           uint32_t* range_cnt, uint32_t* range_off,
-                                           uint32_t* tab_start, uint32_t* tab_end) {
+                                           const AggScratch& sc) {
   if (K_up == 0) {
     if (msg_count != nullptr) return fill_u32(s, msg_count, 1, 0);
     return hipSuccess;
   }
   const uint32_t ranges = aggregate_ranges(d);
-  if (tab_start != nullptr) {
-    k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(up_idx, N, K_up, d,
-                                                                    tab_start, tab_end);
+  const uint32_t blocks = agg_blocks(ranges);
+  uint32_t* any = sc.tab_start != nullptr ? sc.any : nullptr;
+  if (sc.tab_start != nullptr) {
+    k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(
+        up_idx, N, K_up, d, sc.tab_start, sc.tab_end, sc.any);
     hipError_t e0 = hipGetLastError();
     if (e0 != hipSuccess) return e0;
   }
-  k_aggregate<1><<<dim3(ranges), dim3(kAggBlock), 0, s>>>(up_idx, up_val, p, N, K_up, nullptr, d,
-                                                          range_cnt, tab_start, tab_end, nullptr,
-                                                          0.0f, nullptr, nullptr);
+  k_aggregate<1><<<dim3(blocks), dim3(kAggBlock), 0, s>>>(
+      up_idx, up_val, p, N, K_up, nullptr, d, ranges, sc.cnt, sc.tab_start, sc.tab_end, any,
+      nullptr, 0.0f, nullptr, nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k_scan_ranges<<<dim3(1), dim3(1024), 0, s>>>(range_cnt, range_off, ranges, msg_count);
+  k_scan_ranges<<<dim3(1), dim3(1024), 0, s>>>(sc.cnt, sc.off, ranges, msg_count);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k_aggregate<2><<<dim3(ranges), dim3(kAggBlock), 0, s>>>(up_idx, up_val, p, N, K_up, w, d,
-                                                          nullptr, tab_start, tab_end, range_off,
-                                                          -alpha_out, msg_idx, msg_val);
+  k_aggregate<2><<<dim3(blocks), dim3(kAggBlock), 0, s>>>(
+      up_idx, up_val, p, N, K_up, w, d, ranges, nullptr, sc.tab_start, sc.tab_end, any, sc.off,
+      -alpha_out, msg_idx, msg_val);
   return hipGetLastError();
 }
 
