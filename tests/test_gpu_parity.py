@@ -217,6 +217,32 @@ def test_sparse_aggregate(G, oracle, N, d, K):
     G.assert_same_bits(td2, h, "g_t without union_nnz")
 
 
+@pytest.mark.parametrize("N,d,K", [(64, 1500, 4), (130, 5000, 3), (200, 3000, 40)])
+def test_sparse_aggregate_every_worker_names_the_same_coordinates(G, oracle, N, d, K):
+    """The longest possible chain per coordinate: all N workers send the same indices, so
+    every named coordinate takes N dependent fused multiply-adds in ascending q."""
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(7 * N + K)
+    one = np.sort(rng.choice(d, size=K, replace=False)).astype(np.uint32)
+    up_idx = np.tile(one, (N, 1))
+    up_val = rng.standard_normal((N, K)).astype(np.float32)
+    p = rng.dirichlet(np.ones(N)).astype(np.float32)
+    delta = rng.standard_normal(d).astype(np.float32)
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    ti = torch.from_numpy(up_idx.view(np.int32)).to(D)
+    tv, tp, td = (torch.from_numpy(a).to(D) for a in (up_val, p, delta))
+    nnz = torch.zeros(1, dtype=torch.int32, device=D)
+    for _ in range(2):                      # the second call finds the tables and flags clean
+        td.copy_(torch.from_numpy(delta))
+        bts.sparse_aggregate(ctx, ti, tv, tp, td, nnz)
+        torch.cuda.synchronize()
+        h = delta.copy()
+        want_nnz = oracle.aggregate(up_idx, up_val, p, h)
+        G.assert_same_bits(td, h, "g_t")
+        assert int(nnz.item()) == want_nnz == K
+
+
 def test_sparse_sgd_update(G, oracle):
     import paper_2209_15203_amd as bts
     rng = np.random.default_rng(4)
