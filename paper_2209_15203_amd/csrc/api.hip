@@ -79,7 +79,7 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
             dev_alloc(ctx, &sc->lower_key, rows) &&
             dev_alloc(ctx, &sc->cand_cnt, (size_t)rows * fast_sublists() * fast_counter_stride()) &&
             dev_alloc(ctx, &sc->cand, (size_t)rows * fast_sublists() * pl.cap) &&
-            dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_blocks() * 2048) &&
+            dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_words()) &&
             dev_alloc(ctx, &sel, (size_t)rows * fast_sel_bytes()) &&
             dev_alloc(ctx, &sc->need, rows) &&
             dev_alloc(ctx, &sc->dir, (size_t)rows * pl.nwc_pad) &&

@@ -75,9 +75,9 @@ struct FastScratch {
   uint32_t* lower_key;     // rows
   uint32_t* cand_cnt;      // rows x lists, one counter per 128-byte line
   uint2* cand;             // rows x lists x cap (index, value bits)
-  uint32_t* hist;          // rows x fast_hist_blocks() x 2048 partial histograms
+  uint32_t* hist;          // rows x fast_hist_words() partial histograms
   void* sel;               // rows x fast_sel_bytes()
-  uint32_t* need;          // rows: 1 = the dense path must redo this row
+  uint32_t* need;          // rows: nonzero = the dense path must redo this row
   uint2* dir;              // rows x nwc_pad (zero between calls): per wave chunk the start
                            // of its run in its list and the run's length
   void* tile_cnt;          // rows x ntiles 64-bit words (rewritten by every call)
@@ -89,7 +89,7 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K);
 size_t fast_sel_bytes();
 uint32_t fast_sublists();
 uint32_t fast_counter_stride();
-uint32_t fast_hist_blocks();
+size_t fast_hist_words();
 // Same contract as dense_select, except that rows whose need flag is set on return are
 // left unselected (x already holds fma(alpha, g, x) for every row).
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,

@@ -15,8 +15,9 @@
 //   3. verify:   if no list overflowed and the lists hold at least K entries, the K largest
 //                of the row are all listed.  Otherwise the row is flagged and the dense path
 //                (which reads the stored a again) redoes it.  The result never depends on L.
-//   4. select:   exact 11 + 10 + 10 bit radix select of the K-th largest key T over the
-//                lists, and r = how many holders of T are kept.
+//   4. select:   exact radix select of the K-th largest key T over the lists, on key - L in
+//                a 13-bit and a 12-bit digit, and r = how many holders of T are kept (a row
+//                whose T lies more than four octaves above L goes to the dense path too).
 //   5. emit:     the directory in chunk order names the candidates in index order.  Count
 //                the entries greater than / equal to T per tile of 64 chunks, scan the
 //                tiles, then walk each tile again: an entry is kept if it is greater, or
@@ -50,7 +51,7 @@ constexpr int kSliceUnroll = 8;
 // which spreads even clustered hits evenly.
 constexpr uint32_t kSubLists = 64;
 constexpr uint32_t kCounterStride = 32;               // words between two counters
-constexpr uint32_t kMaxHistBlocks = 32;               // blocks per row in a candidate pass
+constexpr uint32_t kMaxHistBlocks = 8;                // blocks per row in a candidate pass
 
 // ---- 1. sample histogram ------------------------------------------------------------
 // Slices are cut at absolute multiples of 256 coordinates (16-byte aligned); only slices
@@ -251,93 +252,56 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
 
 // ---- 3 + 4. verify and select on the candidate lists -------------------------------------
 struct FastSel {
-  uint32_t prefix, k_rem;     // key select in progress
+  uint32_t prefix, k_rem;     // key select in progress: first digit, keys wanted at or below it
   uint32_t T, r;              // threshold key; how many holders of T are kept
 };
 
-// One digit of the select is two kernels: k_cand_hist (a few blocks per row, each
-// histogramming whole lists in LDS and storing its partial histogram with plain stores)
-// and k_cand_scan (one block per row: adds the partials, walks the bins from the top,
-// advances the row's state).  The first histogram kernel also verifies the row: it
-// succeeded when no list overflowed and the lists together hold at least K entries.
-template <int PASS>
-__global__ __launch_bounds__(kBlock) void k_cand_hist(const uint2* __restrict__ cand,
-                                                      const uint32_t* __restrict__ cand_cnt,
-                                                      uint32_t cap, uint32_t K,
-                                                      uint32_t* __restrict__ partial,
-                                                      const FastSel* __restrict__ sel,
-                                                      uint32_t* __restrict__ need) {
-  constexpr int NB = PASS == 0 ? 2048 : 1024;
-  __shared__ uint32_t sh[NB];
-  __shared__ uint32_t s_need;
-  const uint32_t row = blockIdx.y;
-  if (PASS == 0) {
-    if (threadIdx.x < kWave) {
-      const uint32_t c =
-          cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride];
-      const uint32_t total = wave_sum(c);
-      const bool over = __ballot(c > cap) != 0;
-      if (threadIdx.x == 0) {
-        s_need = (over || total < K) ? 1u : 0u;
-        if (blockIdx.x == 0) need[row] = s_need;
-      }
-    }
-    __syncthreads();
-    if (s_need) return;
-  } else if (need[row]) {
-    return;
-  }
-  FastSel s{};
-  if (PASS > 0) s = sel[row];
-  for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
-  __syncthreads();
-  for (uint32_t sl = blockIdx.x; sl < kSubLists; sl += gridDim.x) {
-    const uint64_t sub = (uint64_t)row * kSubLists + sl;
-    const uint32_t cnt = cand_cnt[sub * kCounterStride];
-    const uint2* list = cand + sub * cap;
-    for (uint32_t j = threadIdx.x; j < cnt; j += kBlock) {
-      const uint32_t key = list[j].y & 0x7FFFFFFFu;
-      if (PASS == 0) {
-        atomicAdd(&sh[key >> 20], 1u);
-      } else if (PASS == 1) {
-        if ((key >> 20) == s.prefix) atomicAdd(&sh[(key >> 10) & 1023u], 1u);
-      } else {
-        if ((key >> 10) == s.prefix) atomicAdd(&sh[key & 1023u], 1u);
-      }
-    }
-  }
-  __syncthreads();
-  uint32_t* out = partial + ((uint64_t)row * gridDim.x + blockIdx.x) * 2048;
-  for (int i = threadIdx.x; i < NB; i += kBlock) out[i] = sh[i];
-}
+// Every candidate has key >= L, and the K-th largest key T usually lies within an octave
+// of L, so the select works on off = key - L in two digits: d0 = min(off >> 12, 8191) and
+// d1 = off & 4095.  If T falls into the clamped top bin of d0 (T >= L + 2^25 - 2^12, a
+// bound sixteen times too low) the row is handed to the dense path instead (need = 2).
+//
+//   k_cand_hist0:  verifies the row (no list overflowed, at least K entries: then the K
+//                  largest of the row are all listed; else need = 1) and histograms d0.
+//   k_cand_hist1:  every block resolves d0 from the partial histograms, then histograms d1
+//                  of the entries in d0's bin.
+//   k_cand_finish: one block per row resolves d1: T and r.
+//
+// A few fat blocks per row, each histogramming whole lists in LDS and storing its partial
+// histogram with plain stores: no cross-block atomics, no fences, nothing to clear.
+constexpr int kD1Bits = 12;
+constexpr int kD0Bins = 8192, kD1Bins = 1 << kD1Bits;
+constexpr uint32_t kPartWords = kD0Bins + kD1Bins;    // partial histograms of one block
+constexpr int kCandBlock = 1024;                      // threads per block of the histogram kernels
 
-template <int PASS>
-__global__ __launch_bounds__(kBlock) void k_cand_scan(const uint32_t* __restrict__ partial,
-                                                      uint32_t nparts, uint32_t K,
-                                                      FastSel* __restrict__ sel,
-                                                      const uint32_t* __restrict__ need) {
-  constexpr int NB = PASS == 0 ? 2048 : 1024;
-  constexpr int BPT = NB / kBlock;
-  __shared__ uint32_t lds[kBlock / kWave + 1];
-  const uint32_t row = blockIdx.x;
-  if (need[row]) return;
-  FastSel s{};
-  if (PASS > 0) s = sel[row];
-  const uint32_t want = PASS == 0 ? K : s.k_rem;
+// Adds up the nparts partial NB-bin histograms (stride kPartWords) and walks the bins from
+// the top to the one holding the `want`-th largest entry; *above = entries in higher bins.
+// All threads of the block call this; the result is returned to every thread.
+template <int NB, int THREADS>
+__device__ __forceinline__ uint32_t resolve_partials(const uint32_t* __restrict__ part,
+                                                     uint32_t nparts, uint32_t want,
+                                                     uint32_t* lds, uint32_t* s_out,
+                                                     uint32_t* above) {
+  constexpr int BPT = NB / THREADS;
   const int top = NB - 1 - (int)threadIdx.x * BPT;       // this thread's highest bin
   uint32_t c[BPT];
-  uint32_t sum = 0;
 #pragma unroll
   for (int i = 0; i < BPT; ++i) c[i] = 0;
   for (uint32_t b = 0; b < nparts; ++b) {
-    const uint32_t* h = partial + ((uint64_t)row * nparts + b) * 2048;
+    const uint32_t* h = part + (uint64_t)b * kPartWords;
 #pragma unroll
     for (int i = 0; i < BPT; ++i) c[i] += h[top - i];
   }
+  uint32_t sum = 0;
 #pragma unroll
   for (int i = 0; i < BPT; ++i) sum += c[i];
   uint32_t total;
   const uint32_t excl = block_exclusive_scan(sum, lds, &total);
+  if (threadIdx.x == 0) {                                 // want > total: nothing to find
+    s_out[0] = 0;
+    s_out[1] = 0;
+  }
+  __syncthreads();
   if (excl < want && want <= excl + sum) {                // exactly one thread
     uint32_t acc = excl;
     int bin = top;
@@ -349,18 +313,111 @@ __global__ __launch_bounds__(kBlock) void k_cand_scan(const uint32_t* __restrict
       }
       acc += c[i];
     }
-    const uint32_t b = (uint32_t)bin;
-    if (PASS == 0) {
-      s.prefix = b;
-      s.k_rem = K - acc;
-    } else if (PASS == 1) {
-      s.prefix = (s.prefix << 10) | b;
-      s.k_rem -= acc;
-    } else {
-      s.T = (s.prefix << 10) | b;
-      s.r = s.k_rem - acc;
+    s_out[0] = (uint32_t)bin;
+    s_out[1] = acc;
+  }
+  __syncthreads();
+  const uint32_t bin = s_out[0];
+  *above = s_out[1];
+  __syncthreads();
+  return bin;
+}
+
+__global__ __launch_bounds__(kCandBlock) void k_cand_hist0(const uint2* __restrict__ cand,
+                                                       const uint32_t* __restrict__ cand_cnt,
+                                                       uint32_t cap, uint32_t K,
+                                                       const uint32_t* __restrict__ lower_key,
+                                                       uint32_t* __restrict__ partial,
+                                                       uint32_t* __restrict__ need) {
+  __shared__ uint32_t sh[kD0Bins];
+  __shared__ uint32_t s_need;
+  const uint32_t row = blockIdx.y;
+  if (threadIdx.x < kWave) {
+    const uint32_t c = cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride];
+    const uint32_t total = wave_sum(c);
+    const bool over = __ballot(c > cap) != 0;
+    if (threadIdx.x == 0) {
+      s_need = (over || total < K) ? 1u : 0u;
+      if (blockIdx.x == 0) need[row] = s_need;
     }
-    sel[row] = s;
+  }
+  for (int i = threadIdx.x; i < kD0Bins; i += kCandBlock) sh[i] = 0;
+  __syncthreads();
+  if (s_need) return;
+  const uint32_t L = lower_key[row];
+  // a wave per list
+  for (uint32_t sl = blockIdx.x + gridDim.x * (threadIdx.x / kWave); sl < kSubLists;
+       sl += gridDim.x * (kCandBlock / kWave)) {
+    const uint64_t sub = (uint64_t)row * kSubLists + sl;
+    const uint32_t cnt = cand_cnt[sub * kCounterStride];
+    const uint2* list = cand + sub * cap;
+    for (uint32_t j = lane_id(); j < cnt; j += kWave) {
+      const uint32_t off = (list[j].y & 0x7FFFFFFFu) - L;
+      atomicAdd(&sh[min(off >> kD1Bits, (uint32_t)kD0Bins - 1)], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* out = partial + ((uint64_t)row * gridDim.x + blockIdx.x) * kPartWords;
+  for (int i = threadIdx.x; i < kD0Bins; i += kCandBlock) out[i] = sh[i];
+}
+
+__global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restrict__ cand,
+                                                       const uint32_t* __restrict__ cand_cnt,
+                                                       uint32_t cap, uint32_t K,
+                                                       const uint32_t* __restrict__ lower_key,
+                                                       uint32_t* __restrict__ partial,
+                                                       FastSel* __restrict__ sel,
+                                                       uint32_t* __restrict__ need) {
+  __shared__ uint32_t sh[kD1Bins];
+  __shared__ uint32_t lds[kCandBlock / kWave + 1];
+  __shared__ uint32_t s_out[2];
+  const uint32_t row = blockIdx.y;
+  if (need[row] == 1u) return;             // set by the previous kernel; 2 is set below
+  uint32_t* part_row = partial + (uint64_t)row * gridDim.x * kPartWords;
+  uint32_t above;
+  const uint32_t b0 = resolve_partials<kD0Bins, kCandBlock>(part_row, gridDim.x, K, lds, s_out, &above);
+  if (b0 == (uint32_t)kD0Bins - 1) {       // T is beyond the window: the dense path redoes the row
+    if (blockIdx.x == 0 && threadIdx.x == 0) need[row] = 2u;
+    return;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    sel[row].prefix = b0;
+    sel[row].k_rem = K - above;
+  }
+  for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) sh[i] = 0;
+  __syncthreads();
+  const uint32_t L = lower_key[row];
+  for (uint32_t sl = blockIdx.x + gridDim.x * (threadIdx.x / kWave); sl < kSubLists;
+       sl += gridDim.x * (kCandBlock / kWave)) {
+    const uint64_t sub = (uint64_t)row * kSubLists + sl;
+    const uint32_t cnt = cand_cnt[sub * kCounterStride];
+    const uint2* list = cand + sub * cap;
+    for (uint32_t j = lane_id(); j < cnt; j += kWave) {
+      const uint32_t off = (list[j].y & 0x7FFFFFFFu) - L;
+      if ((off >> kD1Bits) == b0) atomicAdd(&sh[off & (kD1Bins - 1)], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* out = part_row + (uint64_t)blockIdx.x * kPartWords + kD0Bins;
+  for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) out[i] = sh[i];
+}
+
+__global__ __launch_bounds__(kBlock) void k_cand_finish(const uint32_t* __restrict__ partial,
+                                                        uint32_t nparts,
+                                                        const uint32_t* __restrict__ lower_key,
+                                                        FastSel* __restrict__ sel,
+                                                        const uint32_t* __restrict__ need) {
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  __shared__ uint32_t s_out[2];
+  const uint32_t row = blockIdx.x;
+  if (need[row]) return;
+  const FastSel s = sel[row];
+  uint32_t above;
+  const uint32_t b1 = resolve_partials<kD1Bins, kBlock>(
+      partial + (uint64_t)row * nparts * kPartWords + kD0Bins, nparts, s.k_rem, lds, s_out, &above);
+  if (threadIdx.x == 0) {
+    sel[row].T = lower_key[row] + ((s.prefix << kD1Bits) | b1);
+    sel[row].r = s.k_rem - above;
   }
 }
 
@@ -611,23 +668,21 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
         nullptr, x, d, 0.0f, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad);
   BTS_LAUNCH_CHECK();
   if (ev1) (void)hipEventRecord(ev1, s);
-  // 3 + 4. verify and select: a few blocks per row, each taking whole lists (about 4096
-  // entries per block)
-  uint32_t hb = (uint32_t)(((uint64_t)pl.cap * kSubLists / 2 + 4095) / 4096);
+  // 3 + 4. verify and select: a few fat blocks per row, each taking whole lists (about 32768
+  // entries of capacity per block)
+  uint32_t hb = (uint32_t)(((uint64_t)pl.cap * kSubLists / 2 + 32767) / 32768);
   if (hb > kMaxHistBlocks) hb = kMaxHistBlocks;
   if (hb < 1) hb = 1;
   const dim3 hgrid(hb, rows);
   FastSel* sel = reinterpret_cast<FastSel*>(sc.sel);
-#define BTS_CAND_PASS(P)                                                                     \
-  k_cand_hist<P><<<hgrid, block, 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.hist, sel,      \
-                                         sc.need);                                           \
-  BTS_LAUNCH_CHECK();                                                                        \
-  k_cand_scan<P><<<dim3(rows), block, 0, s>>>(sc.hist, hb, K, sel, sc.need);                 \
+  k_cand_hist0<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key, sc.hist,
+                                       sc.need);
   BTS_LAUNCH_CHECK();
-  BTS_CAND_PASS(0)
-  BTS_CAND_PASS(1)
-  BTS_CAND_PASS(2)
-#undef BTS_CAND_PASS
+  k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key, sc.hist,
+                                       sel, sc.need);
+  BTS_LAUNCH_CHECK();
+  k_cand_finish<<<dim3(rows), block, 0, s>>>(sc.hist, hb, sc.lower_key, sel, sc.need);
+  BTS_LAUNCH_CHECK();
   // 5. emit
   const dim3 tgrid((pl.ntiles + kWavesPerBlock - 1) / kWavesPerBlock, rows);
   k_dir_count<<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
@@ -645,6 +700,6 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
 size_t fast_sel_bytes() { return sizeof(FastSel); }
 uint32_t fast_sublists() { return kSubLists; }
 uint32_t fast_counter_stride() { return kCounterStride; }
-uint32_t fast_hist_blocks() { return kMaxHistBlocks; }
+size_t fast_hist_words() { return (size_t)kMaxHistBlocks * kPartWords; }
 
 }  // namespace bts

@@ -128,6 +128,45 @@ def test_threshold_run_spanning_many_workgroups(G, oracle):
         G.assert_same_bits(t, h, f"K={K} residual")
 
 
+def test_threshold_far_above_the_sampled_bound_goes_to_the_dense_path(G, oracle):
+    """The single-pass select works in a window of four octaves above its sampled lower
+    bound.  Here 1.5 K spikes of magnitude 1e3..2e3 sit on N(0,1) noise: the sample puts
+    the bound into the noise tail, the K-th largest is a spike, far beyond the window, so
+    the rows must be handed to the dense path -- and the result is still the oracle's."""
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(31)
+    N, d, K = 3, 1 << 20, 1024
+    g = rng.standard_normal((N, d)).astype(np.float32)
+    for q in range(N):
+        at = rng.choice(d, size=3 * K // 2, replace=False)
+        g[q, at] = (rng.uniform(1e3, 2e3, size=at.size) * rng.choice([-1.0, 1.0], size=at.size)
+                    ).astype(np.float32)
+    e = np.zeros_like(g)
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    ctx.set_path(SINGLE_PASS)
+    tg, te = torch.from_numpy(g).to(D), torch.from_numpy(e).to(D)
+    ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+    bts.topk_compress(ctx, tg, te, 1.0, ui, uv)
+    torch.cuda.synchronize()
+    assert ctx.last_path(0) == (0, N), "every row should have left the window"
+    h = e.copy()
+    wi, wv = oracle.worker_stage(g, h, 1.0, K)
+    G.assert_same_bits(ui, wi, "up_idx")
+    G.assert_same_bits(uv, wv, "up_val")
+    G.assert_same_bits(te, h, "eps")
+    # the same context then serves an ordinary batch in one pass again
+    g2 = rng.standard_normal((N, d)).astype(np.float32)
+    tg2 = torch.from_numpy(g2).to(D)
+    bts.topk_compress(ctx, tg2, te, 1.0, ui, uv)
+    torch.cuda.synchronize()
+    assert ctx.last_path(0) == (N, 0)
+    wi, wv = oracle.worker_stage(g2, h, 1.0, K)
+    G.assert_same_bits(ui, wi, "up_idx, second batch")
+    G.assert_same_bits(te, h, "eps, second batch")
+
+
 @pytest.mark.parametrize("d,path", [(9001, DENSE), (200_001, DENSE), (200_001, SINGLE_PASS)])
 def test_special_values_are_ordered_by_magnitude_bits(G, oracle, d, path):
     """NaN > Inf > finite > denormal > zero, +0 ties with -0, values copied bit for bit."""
