@@ -146,6 +146,8 @@ int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha,
   if (K == 0) {
     if (g == nullptr) return BTS_OK;
     e = axpy_only(ctx->stream, g, x, rows, ctx->d, alpha, e0, e1);
+  } else if (ctx->path_mode == 0 && row_select_fits(ctx->d)) {
+    e = row_select(ctx->stream, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
   } else if (use_fast(ctx, pl)) {
     e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
     if (e == hipSuccess)

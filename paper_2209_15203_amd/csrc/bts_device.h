@@ -66,6 +66,56 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* l
   return res;
 }
 
+// Adds up nparts partial NB-bin histograms (part + b * stride, b < nparts; global memory or
+// LDS) and walks the bins from the top to the one holding the `want`-th largest entry;
+// *above = entries in higher bins.  All THREADS threads of the block call this; the result is
+// returned to every thread.  lds: THREADS / 64 + 1 words, s_out: 2 words.
+template <int NB, int THREADS>
+__device__ __forceinline__ uint32_t resolve_bins(const uint32_t* part, uint32_t nparts,
+                                                 uint32_t stride, uint32_t want, uint32_t* lds,
+                                                 uint32_t* s_out, uint32_t* above) {
+  static_assert(NB % THREADS == 0, "whole bins per thread");
+  constexpr int BPT = NB / THREADS;
+  const int top = NB - 1 - (int)threadIdx.x * BPT;       // this thread's highest bin
+  uint32_t c[BPT];
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) c[i] = 0;
+  for (uint32_t b = 0; b < nparts; ++b) {
+    const uint32_t* h = part + (uint64_t)b * stride;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) c[i] += h[top - i];
+  }
+  uint32_t sum = 0;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) sum += c[i];
+  uint32_t total;
+  const uint32_t excl = block_exclusive_scan(sum, lds, &total);
+  if (threadIdx.x == 0) {                                 // want > total: nothing to find
+    s_out[0] = 0;
+    s_out[1] = 0;
+  }
+  __syncthreads();
+  if (excl < want && want <= excl + sum) {                // exactly one thread
+    uint32_t acc = excl;
+    int bin = top;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) {
+      if (acc + c[i] >= want) {
+        bin = top - i;
+        break;
+      }
+      acc += c[i];
+    }
+    s_out[0] = (uint32_t)bin;
+    s_out[1] = acc;
+  }
+  __syncthreads();
+  const uint32_t bin = s_out[0];
+  *above = s_out[1];
+  __syncthreads();
+  return bin;
+}
+
 // Geometry of one wave-chunk.  Row q covers the absolute element range [lo, hi) of the
 // rows x d matrix; wave-chunks are cut at absolute multiples of kWaveChunk so that every
 // float4 access is 16-byte aligned whatever d is; the first and last chunk of a row are

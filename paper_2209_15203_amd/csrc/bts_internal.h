@@ -59,6 +59,13 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
                      float alpha, hipEvent_t ev0, hipEvent_t ev1);
 
+// ---- short rows: one workgroup per row, one launch (d <= 8192) -------------------------------
+bool row_select_fits(uint64_t d);
+// Same contract as dense_select without the row mask.
+hipError_t row_select(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
+                      uint32_t K, float alpha, uint32_t* out_idx, float* out_val,
+                      hipEvent_t ev0, hipEvent_t ev1);
+
 // ---- speculative single-pass select (exact; flags rows it cannot finish) -----------------
 struct FastPlan {
   bool enabled;            // false: shape is served by the dense path alone (no scratch)

@@ -398,9 +398,11 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need);
   BTS_LAUNCH_CHECK();
   const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
-  k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
-                                                        sc.tile_sums, need);
-  BTS_LAUNCH_CHECK();
+  if (ntiles > 1) {                                // a single tile starts from zero
+    k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
+                                                          sc.tile_sums, need);
+    BTS_LAUNCH_CHECK();
+  }
   k_scan_chunks<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
                                                           sc.tile_sums, need);
   BTS_LAUNCH_CHECK();

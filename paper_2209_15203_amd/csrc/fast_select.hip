@@ -274,55 +274,6 @@ constexpr int kD0Bins = 8192, kD1Bins = 1 << kD1Bits;
 constexpr uint32_t kPartWords = kD0Bins + kD1Bins;    // partial histograms of one block
 constexpr int kCandBlock = 1024;                      // threads per block of the histogram kernels
 
-// Adds up the nparts partial NB-bin histograms (stride kPartWords) and walks the bins from
-// the top to the one holding the `want`-th largest entry; *above = entries in higher bins.
-// All threads of the block call this; the result is returned to every thread.
-template <int NB, int THREADS>
-__device__ __forceinline__ uint32_t resolve_partials(const uint32_t* __restrict__ part,
-                                                     uint32_t nparts, uint32_t want,
-                                                     uint32_t* lds, uint32_t* s_out,
-                                                     uint32_t* above) {
-  constexpr int BPT = NB / THREADS;
-  const int top = NB - 1 - (int)threadIdx.x * BPT;       // this thread's highest bin
-  uint32_t c[BPT];
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) c[i] = 0;
-  for (uint32_t b = 0; b < nparts; ++b) {
-    const uint32_t* h = part + (uint64_t)b * kPartWords;
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) c[i] += h[top - i];
-  }
-  uint32_t sum = 0;
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) sum += c[i];
-  uint32_t total;
-  const uint32_t excl = block_exclusive_scan(sum, lds, &total);
-  if (threadIdx.x == 0) {                                 // want > total: nothing to find
-    s_out[0] = 0;
-    s_out[1] = 0;
-  }
-  __syncthreads();
-  if (excl < want && want <= excl + sum) {                // exactly one thread
-    uint32_t acc = excl;
-    int bin = top;
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) {
-      if (acc + c[i] >= want) {
-        bin = top - i;
-        break;
-      }
-      acc += c[i];
-    }
-    s_out[0] = (uint32_t)bin;
-    s_out[1] = acc;
-  }
-  __syncthreads();
-  const uint32_t bin = s_out[0];
-  *above = s_out[1];
-  __syncthreads();
-  return bin;
-}
-
 __global__ __launch_bounds__(kCandBlock) void k_cand_hist0(const uint2* __restrict__ cand,
                                                        const uint32_t* __restrict__ cand_cnt,
                                                        uint32_t cap, uint32_t K,
@@ -375,7 +326,7 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   if (need[row] == 1u) return;             // set by the previous kernel; 2 is set below
   uint32_t* part_row = partial + (uint64_t)row * gridDim.x * kPartWords;
   uint32_t above;
-  const uint32_t b0 = resolve_partials<kD0Bins, kCandBlock>(part_row, gridDim.x, K, lds, s_out, &above);
+  const uint32_t b0 = resolve_bins<kD0Bins, kCandBlock>(part_row, gridDim.x, kPartWords, K, lds, s_out, &above);
   if (b0 == (uint32_t)kD0Bins - 1) {       // T is beyond the window: the dense path redoes the row
     if (blockIdx.x == 0 && threadIdx.x == 0) need[row] = 2u;
     return;
@@ -413,8 +364,9 @@ __global__ __launch_bounds__(kBlock) void k_cand_finish(const uint32_t* __restri
   if (need[row]) return;
   const FastSel s = sel[row];
   uint32_t above;
-  const uint32_t b1 = resolve_partials<kD1Bins, kBlock>(
-      partial + (uint64_t)row * nparts * kPartWords + kD0Bins, nparts, s.k_rem, lds, s_out, &above);
+  const uint32_t b1 = resolve_bins<kD1Bins, kBlock>(
+      partial + (uint64_t)row * nparts * kPartWords + kD0Bins, nparts, kPartWords, s.k_rem, lds,
+      s_out, &above);
   if (threadIdx.x == 0) {
     sel[row].T = lower_key[row] + ((s.prefix << kD1Bits) | b1);
     sel[row].r = s.k_rem - above;

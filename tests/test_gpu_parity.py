@@ -29,8 +29,10 @@ SHAPES = [
     (1, 1, 1), (3, 5, 2), (2, 63, 7), (4, 1000, 10), (3, 2049, 33), (5, 4099, 4099),
     (2, 10007, 1), (7, 30011, 301), (4, 65536, 66), (3, 100003, 1001), (2, 262147, 5000),
     (1, 70001, 1), (5, 65537, 1024), (2, 262147, 3000), (3, 1048579, 1049), (9, 300001, 37),
+    # the one-workgroup-per-row path ends at d = 8192
+    (64, 8192, 82), (3, 8191, 8191), (2, 7000, 1), (2, 8193, 9),
 ]
-DENSE, SINGLE_PASS = 1, 2
+AUTO, DENSE, SINGLE_PASS = 0, 1, 2      # AUTO: by shape (one workgroup per row up to d = 8192)
 
 
 def make_rows(rng, kind, N, d):
@@ -52,9 +54,11 @@ def make_rows(rng, kind, N, d):
 
 @pytest.mark.parametrize("N,d,K", SHAPES)
 @pytest.mark.parametrize("kind", ["normal", "ties", "quantized", "mixed"])
-@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS])
+@pytest.mark.parametrize("path", [AUTO, DENSE, SINGLE_PASS])
 def test_topk_compress(G, oracle, N, d, K, kind, path):
     import paper_2209_15203_amd as bts
+    if path == AUTO and d > 8192:
+        pytest.skip("by shape this is the dense or the single-pass path, both covered")
     rng = np.random.default_rng(N * 1000003 + d * 7 + K)
     g, eps0, alpha = make_rows(rng, kind, N, d)
     D = G.dev()
