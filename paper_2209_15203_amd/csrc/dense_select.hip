@@ -26,6 +26,7 @@ __device__ __forceinline__ bool row_needed(RowMask need, uint32_t row) {
 // histograms itself at its start (every block, redundantly: a few thousand loads), which
 // saves a separate launch per digit.
 constexpr int kRowHist = kBins0 + 2 * kBinsLo;     // words of histogram per row
+constexpr int kHistCopies = 4;                     // LDS copies of the first digit's histogram
 
 // Walk an NB-bin histogram from the top bin down and find the bin holding the `want`-th
 // largest key; *above = keys in higher bins.  All threads of the block call this; the result
@@ -104,13 +105,18 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
                                                  uint32_t K, uint32_t* __restrict__ hist,
                                                  uint32_t nwc, RowMask need) {
   constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
-  __shared__ uint32_t sh[NB];
+  // The first digit (exponent and three mantissa bits) has a handful of busy bins: the
+  // lanes of a wave spread over COPIES copies of the histogram so that fewer of them meet
+  // on one LDS word.
+  constexpr int COPIES = DIGIT == 0 ? kHistCopies : 1;
+  __shared__ uint32_t sh_all[COPIES * NB];
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
   uint32_t* hist_row = hist + (uint64_t)row * kRowHist;
-  for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
+  for (int i = threadIdx.x; i < COPIES * NB; i += kBlock) sh_all[i] = 0;
+  uint32_t* sh = sh_all + (threadIdx.x % COPIES) * NB;
   const uint32_t prefix = resolve_row<DIGIT>(hist_row, K, lds, s_out).prefix;
   __syncthreads();
   // Bin 0 is counted per lane: a sparse row (the server's g_t is mostly exact zeros) would
@@ -148,7 +154,9 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
   __syncthreads();
   uint32_t* h = hist_row + (DIGIT == 0 ? 0 : (DIGIT == 1 ? kBins0 : kBins0 + kBinsLo));
   for (int i = threadIdx.x; i < NB; i += kBlock) {
-    const uint32_t v = sh[i];
+    uint32_t v = 0;
+#pragma unroll
+    for (int c = 0; c < COPIES; ++c) v += sh_all[c * NB + i];
     if (v) atomicAdd(&h[i], v);
   }
 }
@@ -368,8 +376,10 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   // most rows leave at once, which keeps idle launches cheap.
   uint32_t gx = (nwc + kWavesPerBlock - 1) / kWavesPerBlock;
   {
-    // at least 256 blocks per row, so that a lone row that falls back still streams fast
-    uint32_t lim = 2048u / rows;
+    // at least 256 blocks per row, so that a lone row that falls back still streams fast;
+    // a single row gets 512 (measured at d = 1.1e7: 512 blocks beat 256 by their streaming,
+    // 2048 and 4096 lose 40 and 120 us per select to the flush into the row's histogram)
+    uint32_t lim = 512u / rows;
     if (lim < 256u) lim = 256u;
     if (gx > lim) gx = lim;
   }
