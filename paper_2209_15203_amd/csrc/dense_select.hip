@@ -26,7 +26,6 @@ __device__ __forceinline__ bool row_needed(RowMask need, uint32_t row) {
 // histograms itself at its start (every block, redundantly: a few thousand loads), which
 // saves a separate launch per digit.
 constexpr int kRowHist = kBins0 + 2 * kBinsLo;     // words of histogram per row
-constexpr int kHistCopies = 4;                     // LDS copies of the first digit's histogram
 
 // Walk an NB-bin histogram from the top bin down and find the bin holding the `want`-th
 // largest key; *above = keys in higher bins.  All threads of the block call this; the result
@@ -105,18 +104,13 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
                                                  uint32_t K, uint32_t* __restrict__ hist,
                                                  uint32_t nwc, RowMask need) {
   constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
-  // The first digit (exponent and three mantissa bits) has a handful of busy bins: the
-  // lanes of a wave spread over COPIES copies of the histogram so that fewer of them meet
-  // on one LDS word.
-  constexpr int COPIES = DIGIT == 0 ? kHistCopies : 1;
-  __shared__ uint32_t sh_all[COPIES * NB];
+  __shared__ uint32_t sh[NB];
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
   uint32_t* hist_row = hist + (uint64_t)row * kRowHist;
-  for (int i = threadIdx.x; i < COPIES * NB; i += kBlock) sh_all[i] = 0;
-  uint32_t* sh = sh_all + (threadIdx.x % COPIES) * NB;
+  for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
   const uint32_t prefix = resolve_row<DIGIT>(hist_row, K, lds, s_out).prefix;
   __syncthreads();
   // Bin 0 is counted per lane: a sparse row (the server's g_t is mostly exact zeros) would
@@ -154,9 +148,7 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
   __syncthreads();
   uint32_t* h = hist_row + (DIGIT == 0 ? 0 : (DIGIT == 1 ? kBins0 : kBins0 + kBinsLo));
   for (int i = threadIdx.x; i < NB; i += kBlock) {
-    uint32_t v = 0;
-#pragma unroll
-    for (int c = 0; c < COPIES; ++c) v += sh_all[c * NB + i];
+    const uint32_t v = sh[i];
     if (v) atomicAdd(&h[i], v);
   }
 }
