@@ -301,21 +301,56 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
   if (MODE == 0 && nnz_out != nullptr && lane == 0) nnz_out[g] = nnz;
 }
 
-// Exclusive scan of the per-range counts (one block); *total_out receives the sum.
+// Exclusive scan of the per-range counts (one block of 16 waves); *total_out receives the
+// sum.  Each wave owns a contiguous segment (a multiple of 256 counts) and goes through it
+// 256 counts at a time, four per lane from one 16-byte load: first for the segment's sum,
+// then, from the sum of the segments before it, for the offsets.
 __global__ __launch_bounds__(1024) void k_scan_ranges(const uint32_t* __restrict__ cnt,
                                                       uint32_t* __restrict__ off, uint32_t n,
                                                       uint32_t* __restrict__ total_out) {
-  __shared__ uint32_t lds[1024 / kWave + 1];
-  const uint32_t per = (n + blockDim.x - 1) / blockDim.x;
-  const uint32_t b = min(threadIdx.x * per, n), e = min(b + per, n);
-  uint32_t s = 0;
-  for (uint32_t i = b; i < e; ++i) s += cnt[i];
-  uint32_t total;
-  uint32_t run = block_exclusive_scan(s, lds, &total);
-  for (uint32_t i = b; i < e; ++i) {
-    const uint32_t t = cnt[i];
-    off[i] = run;
-    run += t;
+  constexpr uint32_t kWaves = 1024 / kWave, kStep = kWave * 4;
+  __shared__ uint32_t s_tot[kWaves];
+  const uint32_t w = threadIdx.x / kWave, lane = lane_id();
+  const uint32_t seg = ((n + kWaves - 1) / kWaves + kStep - 1) / kStep * kStep;
+  const uint64_t b = (uint64_t)w * seg;
+  const uint64_t e = min(b + seg, (uint64_t)n);
+  auto load4 = [&](uint64_t i, uint32_t (&v)[4]) {
+    if (i + 4 <= e) {
+      const uint4 q = *reinterpret_cast<const uint4*>(cnt + i);
+      v[0] = q.x, v[1] = q.y, v[2] = q.z, v[3] = q.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = i + j < e ? cnt[i + j] : 0u;
+    }
+  };
+  uint32_t sum = 0;
+  for (uint64_t i = b + lane * 4; i < e; i += kStep) {
+    uint32_t v[4];
+    load4(i, v);
+    sum += v[0] + v[1] + v[2] + v[3];
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) s_tot[w] = sum;
+  __syncthreads();
+  uint32_t run = 0, total = 0;
+  for (uint32_t i = 0; i < kWaves; ++i) {
+    const uint32_t t = s_tot[i];
+    if (i < w) run += t;
+    total += t;
+  }
+  for (uint64_t i0 = b; i0 < e; i0 += kStep) {
+    const uint64_t i = i0 + lane * 4;
+    uint32_t v[4];
+    load4(i, v);
+    const uint32_t mine = v[0] + v[1] + v[2] + v[3];
+    const uint32_t incl = wave_inclusive_scan(mine);
+    uint32_t at = run + incl - mine;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (i + j < e) off[i + j] = at;
+      at += v[j];
+    }
+    run += __shfl(incl, kWave - 1, kWave);
   }
   if (threadIdx.x == 0 && total_out != nullptr) *total_out = total;
 }
