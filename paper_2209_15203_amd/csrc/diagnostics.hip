@@ -59,8 +59,9 @@ __global__ __launch_bounds__(kBlock) void k_diag_dense(
     for (uint32_t q = 0; q < N; ++q) {
       float gq[VEC], eq[VEC];
       if (VEC == 4) {
-        const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + (uint64_t)q * d + i));
-        const f4 ev = __builtin_nontemporal_load(reinterpret_cast<const f4*>(eps + (uint64_t)q * d + i));
+        const uint64_t at = (uint64_t)q * d + i;
+        const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + at));
+        const f4 ev = __builtin_nontemporal_load(reinterpret_cast<const f4*>(eps + at));
         gq[0] = gv.x; gq[1 % VEC] = gv.y; gq[2 % VEC] = gv.z; gq[3 % VEC] = gv.w;
         eq[0] = ev.x; eq[1 % VEC] = ev.y; eq[2 % VEC] = ev.z; eq[3 % VEC] = ev.w;
       } else {

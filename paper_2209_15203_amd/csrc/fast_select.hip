@@ -326,7 +326,8 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   if (need[row] == 1u) return;             // set by the previous kernel; 2 is set below
   uint32_t* part_row = partial + (uint64_t)row * gridDim.x * kPartWords;
   uint32_t above;
-  const uint32_t b0 = resolve_bins<kD0Bins, kCandBlock>(part_row, gridDim.x, kPartWords, K, lds, s_out, &above);
+  const uint32_t b0 =
+      resolve_bins<kD0Bins, kCandBlock>(part_row, gridDim.x, kPartWords, K, lds, s_out, &above);
   if (b0 == (uint32_t)kD0Bins - 1) {       // T is beyond the window: the dense path redoes the row
     if (blockIdx.x == 0 && threadIdx.x == 0) need[row] = 2u;
     return;
@@ -376,10 +377,10 @@ __global__ __launch_bounds__(kBlock) void k_cand_finish(const uint32_t* __restri
 // ---- 5. ordered emission through the chunk directory -------------------------------------
 // The directory lists a row's runs in chunk order, and a run holds its entries in index
 // order, so walking the directory visits the row's candidates in index order; nothing has
-// to be sorted and no atomics are needed.  A wave owns a tile of 64 consecutive chunks
-// (chunk wc appends to list wc % 64, so lane l's chunk always uses list l): it scans the
-// run lengths, then its lanes take the tile's entries round-robin in that order, finding
-// an entry's run by bisection on the scanned lengths.
+// to be sorted and no atomics are needed.  A wave works on a tile of 64 consecutive chunks
+// at a time (chunk wc appends to list wc % 64, so lane l's chunk always uses list l): it
+// scans the run lengths, then its lanes take the tile's entries round-robin in that order,
+// finding an entry's run by bisection on the scanned lengths.
 //
 //   k_dir_count: per tile, how many entries are greater than T and how many equal T.
 //   k_dir_scan:  per row, exclusive prefix of those pairs over the tiles.
@@ -397,19 +398,26 @@ struct TileView {
   const uint32_t* start;   // per chunk: start of its run in its list (LDS, this wave's)
 };
 
-// Loads the tile's directory entries (one per lane) and publishes the scanned lengths to
-// the wave's part of LDS.  *mine gets the lane's run length.
-__device__ __forceinline__ TileView load_tile(const uint2* __restrict__ dir_row, uint32_t tile,
-                                              uint32_t* lds_off, uint32_t* lds_start,
-                                              uint32_t* mine) {
-  const uint2 ent = dir_row[(uint64_t)tile * kTileChunks + lane_id()];
-  const uint32_t incl = wave_inclusive_scan(ent.y);
-  lds_off[lane_id()] = incl - ent.y;
-  lds_start[lane_id()] = ent.x;
+// Where most tiles are empty (few candidates per tile) a wave takes TPW = 4 tiles, a
+// quarter of the row apart (tile v, v + Q, v + 2Q, v + 3Q, so that a run of busy tiles is
+// spread over many waves), fetches their directory entries together and skips the empty
+// ones without further work; where most tiles are busy a wave takes one.
+
+__device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  *mine = ent.y;
+}
+
+// Publishes the scanned run lengths of a tile (ent = the lane's directory entry) to the
+// wave's part of LDS.
+__device__ __forceinline__ TileView publish_tile(uint2 ent, uint32_t* lds_off,
+                                                 uint32_t* lds_start) {
+  const uint32_t incl = wave_inclusive_scan(ent.y);
+  wave_lds_sync();                               // the previous tile's readers are done
+  lds_off[lane_id()] = incl - ent.y;
+  lds_start[lane_id()] = ent.x;
+  wave_lds_sync();
   TileView t;
   t.total = __shfl(incl, kWave - 1, kWave);
   t.off = lds_off;
@@ -427,6 +435,7 @@ __device__ __forceinline__ uint2 tile_entry(const TileView& t, uint32_t e,
   return cand_row[(uint64_t)c * cap + t.start[c] + (e - t.off[c])];
 }
 
+template <int TPW>
 __global__ __launch_bounds__(kBlock) void k_dir_count(
     const uint2* __restrict__ dir, uint32_t nwc_pad, const uint2* __restrict__ cand,
     uint32_t cap, const FastSel* __restrict__ sel, const uint32_t* __restrict__ need,
@@ -435,32 +444,45 @@ __global__ __launch_bounds__(kBlock) void k_dir_count(
   const uint32_t row = blockIdx.y;
   if (need[row]) return;
   const uint32_t w = threadIdx.x / kWave;
-  const uint32_t tile = blockIdx.x * kWavesPerBlock + w;
-  if (tile >= ntiles) return;
-  uint32_t mine;
-  const TileView t =
-      load_tile(dir + (uint64_t)row * nwc_pad, tile, s_off[w], s_start[w], &mine);
+  const uint32_t quarter = (ntiles + TPW - 1) / TPW;
+  const uint32_t v = blockIdx.x * kWavesPerBlock + w;
+  if (v >= quarter) return;
+  const uint2* dir_row = dir + (uint64_t)row * nwc_pad;
+  uint2 ent[TPW];
+#pragma unroll
+  for (int u = 0; u < TPW; ++u) {
+    const uint32_t tile = v + u * quarter;
+    ent[u] = tile < ntiles ? dir_row[(uint64_t)tile * kTileChunks + lane_id()] : make_uint2(0u, 0u);
+  }
   const uint32_t T = sel[row].T;
   const uint2* cand_row = cand + (uint64_t)row * kSubLists * cap;
-  uint32_t gt = 0, eq = 0;
-  for (uint32_t e0 = 0; e0 < t.total; e0 += kWave * kEmitUnroll) {
-    uint32_t key[kEmitUnroll];
 #pragma unroll
-    for (int u = 0; u < kEmitUnroll; ++u) {
-      const uint32_t e = e0 + u * kWave + lane_id();
-      key[u] = e < t.total ? tile_entry(t, e, cand_row, cap).y & 0x7FFFFFFFu : 0u;
-    }
+  for (int u = 0; u < TPW; ++u) {
+    const uint32_t tile = v + u * quarter;
+    if (tile >= ntiles) break;
+    uint32_t gt = 0, eq = 0;
+    if (__ballot(ent[u].y != 0) != 0) {
+      const TileView t = publish_tile(ent[u], s_off[w], s_start[w]);
+      for (uint32_t e0 = 0; e0 < t.total; e0 += kWave * kEmitUnroll) {
+        uint32_t key[kEmitUnroll];
 #pragma unroll
-    for (int u = 0; u < kEmitUnroll; ++u) {
-      const uint32_t e = e0 + u * kWave + lane_id();
-      gt += (e < t.total && key[u] > T) ? 1u : 0u;
-      eq += (e < t.total && key[u] == T) ? 1u : 0u;
+        for (int k = 0; k < kEmitUnroll; ++k) {
+          const uint32_t e = e0 + k * kWave + lane_id();
+          key[k] = e < t.total ? tile_entry(t, e, cand_row, cap).y & 0x7FFFFFFFu : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kEmitUnroll; ++k) {
+          const uint32_t e = e0 + k * kWave + lane_id();
+          gt += (e < t.total && key[k] > T) ? 1u : 0u;
+          eq += (e < t.total && key[k] == T) ? 1u : 0u;
+        }
+      }
+      gt = wave_sum(gt);
+      eq = wave_sum(eq);
     }
+    if (lane_id() == 0)
+      tile_cnt[(uint64_t)row * ntiles + tile] = ((unsigned long long)eq << 32) | gt;
   }
-  gt = wave_sum(gt);
-  eq = wave_sum(eq);
-  if (lane_id() == 0)
-    tile_cnt[(uint64_t)row * ntiles + tile] = ((unsigned long long)eq << 32) | gt;
 }
 
 // One block per row; every thread owns a contiguous share of the tiles.
@@ -490,6 +512,7 @@ __global__ __launch_bounds__(kBlock) void k_dir_scan(unsigned long long* __restr
   }
 }
 
+template <int TPW>
 __global__ __launch_bounds__(kBlock) void k_dir_emit(
     uint2* __restrict__ dir, uint32_t nwc_pad, const uint2* __restrict__ cand, uint32_t cap,
     const FastSel* __restrict__ sel, const uint32_t* __restrict__ need,
@@ -498,48 +521,60 @@ __global__ __launch_bounds__(kBlock) void k_dir_emit(
   __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
   const uint32_t row = blockIdx.y;
   const uint32_t w = threadIdx.x / kWave;
-  const uint32_t tile = blockIdx.x * kWavesPerBlock + w;
-  if (tile >= ntiles) return;
+  const uint32_t quarter = (ntiles + TPW - 1) / TPW;
+  const uint32_t v = blockIdx.x * kWavesPerBlock + w;
+  if (v >= quarter) return;
   uint2* dir_row = dir + (uint64_t)row * nwc_pad;
-  uint32_t mine;
-  const TileView t = load_tile(dir_row, tile, s_off[w], s_start[w], &mine);
-  if (mine) dir_row[(uint64_t)tile * kTileChunks + lane_id()] = make_uint2(0u, 0u);
-  if (need[row] || t.total == 0) return;
+  uint2 ent[TPW];
+#pragma unroll
+  for (int u = 0; u < TPW; ++u) {
+    const uint32_t tile = v + u * quarter;
+    ent[u] = tile < ntiles ? dir_row[(uint64_t)tile * kTileChunks + lane_id()] : make_uint2(0u, 0u);
+    if (ent[u].y) dir_row[(uint64_t)tile * kTileChunks + lane_id()] = make_uint2(0u, 0u);
+  }
+  if (need[row]) return;
   const FastSel s = sel[row];
-  const unsigned long long before = tile_cnt[(uint64_t)row * ntiles + tile];
-  uint32_t run_gt = (uint32_t)before, run_eq = (uint32_t)(before >> 32);
   const uint2* cand_row = cand + (uint64_t)row * kSubLists * cap;
   float* xr = x + (uint64_t)row * d;
   uint32_t* oi = out_idx + (uint64_t)row * K;
   float* ov = out_val + (uint64_t)row * K;
   const uint64_t below = lanes_below();
-  for (uint32_t e0 = 0; e0 < t.total; e0 += kWave * kEmitUnroll) {
-    uint2 en[kEmitUnroll];
 #pragma unroll
-    for (int u = 0; u < kEmitUnroll; ++u) {
-      const uint32_t e = e0 + u * kWave + lane_id();
-      en[u] = e < t.total ? tile_entry(t, e, cand_row, cap) : make_uint2(0u, 0u);
-    }
+  for (int u = 0; u < TPW; ++u) {
+    const uint32_t tile = v + u * quarter;
+    if (tile >= ntiles) break;
+    if (__ballot(ent[u].y != 0) == 0) continue;
+    const TileView t = publish_tile(ent[u], s_off[w], s_start[w]);
+    const unsigned long long before = tile_cnt[(uint64_t)row * ntiles + tile];
+    uint32_t run_gt = (uint32_t)before, run_eq = (uint32_t)(before >> 32);
+    for (uint32_t e0 = 0; e0 < t.total; e0 += kWave * kEmitUnroll) {
+      uint2 en[kEmitUnroll];
 #pragma unroll
-    for (int u = 0; u < kEmitUnroll; ++u) {
-      const uint32_t e = e0 + u * kWave + lane_id();
-      const uint32_t key = en[u].y & 0x7FFFFFFFu;
-      const bool is_gt = e < t.total && key > s.T;
-      const bool is_eq = e < t.total && key == s.T;
-      const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
-      const uint32_t n_gt = run_gt + __popcll(m_gt & below);       // greater before me
-      const uint32_t n_eq = run_eq + __popcll(m_eq & below);       // equal before me
-      if (is_gt || (is_eq && n_eq < s.r)) {
-        const uint32_t pos = n_gt + min(n_eq, s.r);
-        const uint32_t idx = en[u].x;
-        if (pos < K && idx < d) {
-          oi[pos] = idx;
-          ov[pos] = __uint_as_float(en[u].y);
-          xr[idx] = 0.0f;
-        }
+      for (int k = 0; k < kEmitUnroll; ++k) {
+        const uint32_t e = e0 + k * kWave + lane_id();
+        en[k] = e < t.total ? tile_entry(t, e, cand_row, cap) : make_uint2(0u, 0u);
       }
-      run_gt += __popcll(m_gt);
-      run_eq += __popcll(m_eq);
+#pragma unroll
+      for (int k = 0; k < kEmitUnroll; ++k) {
+        const uint32_t e = e0 + k * kWave + lane_id();
+        const uint32_t key = en[k].y & 0x7FFFFFFFu;
+        const bool is_gt = e < t.total && key > s.T;
+        const bool is_eq = e < t.total && key == s.T;
+        const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+        const uint32_t n_gt = run_gt + __popcll(m_gt & below);       // greater before me
+        const uint32_t n_eq = run_eq + __popcll(m_eq & below);       // equal before me
+        if (is_gt || (is_eq && n_eq < s.r)) {
+          const uint32_t pos = n_gt + min(n_eq, s.r);
+          const uint32_t idx = en[k].x;
+          if (pos < K && idx < d) {
+            oi[pos] = idx;
+            ov[pos] = __uint_as_float(en[k].y);
+            xr[idx] = 0.0f;
+          }
+        }
+        run_gt += __popcll(m_gt);
+        run_eq += __popcll(m_eq);
+      }
     }
   }
 }
@@ -627,23 +662,33 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   if (hb < 1) hb = 1;
   const dim3 hgrid(hb, rows);
   FastSel* sel = reinterpret_cast<FastSel*>(sc.sel);
-  k_cand_hist0<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key, sc.hist,
-                                       sc.need);
+  k_cand_hist0<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
+                                                  sc.hist, sc.need);
   BTS_LAUNCH_CHECK();
-  k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key, sc.hist,
-                                       sel, sc.need);
+  k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
+                                                  sc.hist, sel, sc.need);
   BTS_LAUNCH_CHECK();
   k_cand_finish<<<dim3(rows), block, 0, s>>>(sc.hist, hb, sc.lower_key, sel, sc.need);
   BTS_LAUNCH_CHECK();
   // 5. emit
-  const dim3 tgrid((pl.ntiles + kWavesPerBlock - 1) / kWavesPerBlock, rows);
-  k_dir_count<<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                      tile_cnt, pl.ntiles);
+  const bool sparse_tiles = 3ull * K < 16ull * pl.ntiles;      // under 16 candidates per tile
+  const uint32_t tile_waves = sparse_tiles ? (pl.ntiles + 3) / 4 : pl.ntiles;
+  const dim3 tgrid((tile_waves + kWavesPerBlock - 1) / kWavesPerBlock, rows);
+  if (sparse_tiles)
+    k_dir_count<4><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                           tile_cnt, pl.ntiles);
+  else
+    k_dir_count<1><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                           tile_cnt, pl.ntiles);
   BTS_LAUNCH_CHECK();
   k_dir_scan<<<dim3(rows), block, 0, s>>>(tile_cnt, pl.ntiles, sc.need);
   BTS_LAUNCH_CHECK();
-  k_dir_emit<<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need, tile_cnt,
-                                     pl.ntiles, x, d, K, out_idx, out_val);
+  if (sparse_tiles)
+    k_dir_emit<4><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                          tile_cnt, pl.ntiles, x, d, K, out_idx, out_val);
+  else
+    k_dir_emit<1><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                          tile_cnt, pl.ntiles, x, d, K, out_idx, out_val);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   return hipSuccess;

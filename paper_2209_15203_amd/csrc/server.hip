@@ -146,8 +146,9 @@ __device__ __forceinline__ uint32_t aggregate_range(
           if (L.pref[a + st] <= e) a += st;
         const uint64_t src = (uint64_t)(q0 + a) * K_up + L.lo[a] + (e - L.pref[a]);
         const uint32_t i = up_idx[src];
-        const uint32_t rel = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;   // always in
-        L.e_key[k] = rel | (a << 16);                                             // for sorted input
+        // inside the range for sorted input
+        const uint32_t rel = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;
+        L.e_key[k] = rel | (a << 16);
         if (MODE != 1) L.e_val[k] = up_val[src];
       }
       if (MODE != 1 && lane < kWave) L.lvl_fill[lane] = 0;
