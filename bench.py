@@ -65,6 +65,10 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain copy kernel of known size (2^28 floats read, 2^28 "
                          "written) so that a counter profile of this command can be scaled")
+    ap.add_argument("--probe-hbm", action="store_true",
+                    help="instead of the step: time plain read / copy / fma-stream kernels with "
+                         "the dominant kernel's access shape over the workload's g and eps "
+                         "buffers and print their rates (what the part sustains for each mix)")
     ap.add_argument("--cpu-rows", type=int, default=0)
     ap.add_argument("--algo", choices=["bidir", "unidir", "bidir_diag"], default="bidir",
                     help="bidir: Algorithm 2 (the headline); unidir: Algorithm 1, the paper's "
@@ -169,6 +173,18 @@ def main() -> int:
         delta.zero_()
         w.copy_(wl.weights0(cfg, dev))
         torch.cuda.synchronize()
+
+    if args.probe_hbm:
+        src_p, dst_p = ring[0].view(-1), eps.view(-1)
+        n = src_p.numel() // 512 * 512
+        out = {"probe": "plain streams with the dominant kernel's access shape",
+               "floats": n, "peak_gbps": HBM_PEAK_GBS, "unit": "GB/s"}
+        for kind, name, bytes_per in ((0, "read", 4), (1, "copy", 8), (2, "fma_stream", 12)):
+            ms = ctx.hbm_probe(kind, src_p, dst_p, repeats=max(1, args.steps))
+            out[name] = {"ms": ms, "gbps": bytes_per * n / ms / 1e6,
+                         "frac_of_peak": bytes_per * n / ms / 1e6 / HBM_PEAK_GBS}
+        print(json.dumps(out))
+        return 0
 
     if args.calibrate_copy:
         src_c = torch.ones(1 << 28, dtype=torch.float32, device=dev)

@@ -166,6 +166,18 @@ int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, floa
 int bts_profile_enable(bts_ctx* ctx, int on);
 int bts_profile_read(bts_ctx* ctx, double* ms_total, uint64_t* launches);
 
+/*
+ * Measurement aid: a plain stream over n floats (device pointers, 16-byte aligned, n >= 512;
+ * whole 512-float chunks only) with the dominant kernel's access shape and nothing else:
+ * kind 0 reads src, kind 1 copies src to dst, kind 2 does dst = fma(0.5, src, dst) -- the
+ * 2 reads : 1 write mix of the worker stage (Algorithm 2, worker line 1).  Queues one
+ * untimed launch and `repeats` timed ones on the context's stream, waits for them, and
+ * returns the mean time of one launch in milliseconds (host pointer).  kinds 1 and 2
+ * overwrite dst.  Shows what fraction of the 8 TB/s peak such a stream reaches on the part.
+ */
+int bts_hbm_probe(bts_ctx* ctx, int kind, const float* src, float* dst, uint64_t n,
+                  int repeats, double* ms_per_launch);
+
 /* Path taken by the last topk_compress / downlink_topk on this context, for tests and
  * reports: a host-synchronous read of per-row flags.  rows_fast = rows finished by the
  * single-pass path, rows_dense = all others (dense multi-pass path, or the one-workgroup

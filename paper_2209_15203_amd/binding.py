@@ -12,7 +12,8 @@ _LIB_PATH = os.path.join(_HERE, "libbts.so")
 
 EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
            "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
-           "unidir_step", "bts_enable_diagnostics", "bidir_step_diag", "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path"]
+           "unidir_step", "bts_enable_diagnostics", "bidir_step_diag", "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path",
+           "bts_hbm_probe"]
 
 _lib = None
 
@@ -114,6 +115,15 @@ class BtsContext:
         ms, n = C.c_double(0.0), C.c_uint64(0)
         self.check(self._lib.bts_profile_read(self._h, C.byref(ms), C.byref(n)), "bts_profile_read")
         return ms.value, n.value
+
+    def hbm_probe(self, kind: int, src: torch.Tensor, dst: torch.Tensor, repeats: int = 5) -> float:
+        """Mean milliseconds of one plain stream over src/dst (0 read, 1 copy, 2 fma-stream)."""
+        ms = C.c_double(0.0)
+        n = min(src.numel(), dst.numel())
+        self.check(self._lib.bts_hbm_probe(self._h, int(kind), _ptr(src, torch.float32, "src"),
+                                           _ptr(dst, torch.float32, "dst"), C.c_uint64(n),
+                                           int(repeats), C.byref(ms)), "bts_hbm_probe")
+        return ms.value
 
     def enable_diagnostics(self) -> None:
         self.check(self._lib.bts_enable_diagnostics(self._h), "bts_enable_diagnostics")

@@ -391,6 +391,15 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
   return BTS_OK;
 }
 
+int bts_hbm_probe(bts_ctx* ctx, int kind, const float* src, float* dst, uint64_t n,
+                  int repeats, double* ms_per_launch) {
+  if (!ctx || !src || !dst || !ms_per_launch || kind < 0 || kind > 2 || repeats < 1 || n < 512)
+    return BTS_EINVAL;
+  if (!aligned16(src) || !aligned16(dst)) return BTS_EINVAL;
+  const hipError_t e = hbm_probe(ctx->stream, kind, src, dst, n, 0.5f, repeats, ms_per_launch);
+  return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
+}
+
 int bts_set_path(bts_ctx* ctx, int mode) {
   if (!ctx || mode < 0 || mode > 2) return BTS_EINVAL;
   ctx->path_mode = mode;

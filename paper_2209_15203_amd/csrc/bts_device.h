@@ -33,6 +33,14 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
   return v;
 }
 
+// Orders this wave's LDS accesses across its lanes (the hardware runs a wave's LDS
+// instructions in order; this keeps the compiler from moving them).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Exclusive prefix over lanes of a per-lane count in 0..7, from three ballots.
 __device__ __forceinline__ uint32_t wave_exclusive_small(uint32_t c, uint32_t* total) {
   const uint64_t below = lanes_below();

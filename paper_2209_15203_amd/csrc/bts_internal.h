@@ -151,4 +151,8 @@ hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint
                       float alpha_out, float* w, uint64_t d);
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v);
 
+// Plain streams with the dominant kernel's access shape (kind 0 read, 1 copy, 2 fma-stream).
+hipError_t hbm_probe(hipStream_t s, int kind, const float* src, float* dst, uint64_t n,
+                     float alpha, int repeats, double* ms_per_launch);
+
 }  // namespace bts

@@ -403,12 +403,6 @@ struct TileView {
 // spread over many waves), fetches their directory entries together and skips the empty
 // ones without further work; where most tiles are busy a wave takes one.
 
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Publishes the scanned run lengths of a tile (ent = the lane's directory entry) to the
 // wave's part of LDS.
 __device__ __forceinline__ TileView publish_tile(uint2 ent, uint32_t* lds_off,

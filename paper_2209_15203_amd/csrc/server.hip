@@ -70,14 +70,6 @@ struct AggWaveLds {
   uint16_t order[kAggStage];            // the stage's pairs grouped by depth level
 };
 
-// Orders this wave's LDS accesses across its lanes (the hardware runs a wave's LDS
-// instructions in order; this keeps the compiler from moving them).
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 __device__ __forceinline__ uint32_t seen_byte(const AggWaveLds& L, uint32_t rel) {
   return (L.seen[rel >> 2] >> (8 * (rel & 3))) & 0xFFu;
 }
