@@ -4,6 +4,7 @@ oracle's fp32 chains are exact, so both must agree to fp64 rounding), the degene
 the definitions fix (one worker: rho_hat = 0; K = d: all three are 0), the contraction bound
 of Eq. "topk_bound", and that the step itself is unchanged."""
 import numpy as np
+import pytest
 
 
 def topk_dense(x, K):
@@ -31,9 +32,10 @@ def reference(g, eps, delta, p, alpha, K_up, K_dn):
     return rho, rho_hat, gam_w, gam_s, den, nnz
 
 
-def test_matches_the_written_out_definitions_on_dyadic_inputs(oracle):
+@pytest.mark.parametrize("K_up,K_dn", [(9, 6), (5, 11)])     # either may be the larger one
+def test_matches_the_written_out_definitions_on_dyadic_inputs(oracle, K_up, K_dn):
     rng = np.random.default_rng(31)
-    N, d, K_up, K_dn = 4, 600, 9, 6
+    N, d = 4, 600
     p = np.full(N, 0.25, np.float32)
     alpha = 0.125
     eps = np.zeros((N, d), np.float32)
