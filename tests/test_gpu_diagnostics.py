@@ -49,6 +49,31 @@ def test_diagnostics_scaled_configs(oracle, name):
         assert 0 < got[1] and got[2] <= 1.0
 
 
+def test_diagnostics_uplink_smaller_than_downlink(oracle):
+    """K_up < K_dn: rho's two Top_K use K_dn, rho_hat's uses K_up (the configurations above all
+    have K_up >= K_dn)."""
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    D = G.dev()
+    rng = np.random.default_rng(41)
+    N, d, K_up, K_dn = 5, 40_003, 30, 77
+    p = rng.dirichlet(np.ones(N)).astype(np.float32)
+    st = G.GpuState(N, d, K_up, K_dn, np.zeros(d, np.float32), p)
+    st.ctx.enable_diagnostics()
+    diag = torch.zeros(8 + N, dtype=torch.float64, device=D)
+    for t in range(3):
+        g = rng.standard_normal((N, d)).astype(np.float32)
+        bts.bidir_step_diag(st.ctx, torch.from_numpy(g).to(D), st.eps, st.delta, st.w, st.p, 0.1,
+                            1.0, st.up_idx, st.up_val, st.dn_idx, st.dn_val, diag)
+        torch.cuda.synchronize()
+        want = oracle.bidir_step_diag(g, st.h_eps, st.h_delta, st.h_w, st.h_p, K_up, K_dn, 0.1, 1.0)
+        G.assert_same_bits(st.dn_idx, want["dn_idx"], f"step {t} dn_idx")
+        G.assert_same_bits(st.delta, st.h_delta, f"step {t} delta")
+        G.assert_same_bits(st.w, st.h_w, f"step {t} w")
+        got = diag.cpu().numpy()
+        assert np.allclose(got, want["diag"], rtol=RTOL, atol=0), (t, got[:8], want["diag"][:8])
+
+
 def test_diagnostics_degenerate_cases(oracle):
     import _gpu_util as G
     import paper_2209_15203_amd as bts
