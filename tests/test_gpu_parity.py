@@ -132,6 +132,36 @@ def test_threshold_run_spanning_many_workgroups(G, oracle):
         G.assert_same_bits(t, h, f"K={K} residual")
 
 
+@pytest.mark.parametrize("start", [300_000, 655_360 - 17])
+def test_all_kept_coordinates_in_one_contiguous_block(G, oracle, start):
+    """Every large value sits in one block of 60,000 consecutive coordinates (runs of 512
+    candidates per wave chunk, directory tiles with tens of thousands of entries, a strided
+    sample that may miss the block or land inside it): whichever way the rows finish, the
+    result is the oracle's."""
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(start)
+    N, d, K = 3, 1 << 20, 40_000
+    g = (rng.standard_normal((N, d)) * 1e-3).astype(np.float32)
+    for q in range(N):
+        block = rng.permutation(60_000).astype(np.float32) + 1000.0      # distinct magnitudes
+        g[q, start + 7 * q:start + 7 * q + 60_000] = block * rng.choice([-1.0, 1.0], size=60_000)
+    e = np.zeros_like(g)
+    D = G.dev()
+    for path in (SINGLE_PASS, DENSE):
+        ctx = bts.BtsContext(N, d, K, K)
+        ctx.set_path(path)
+        tg, te = torch.from_numpy(g).to(D), torch.from_numpy(e).to(D)
+        ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+        uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+        bts.topk_compress(ctx, tg, te, 1.0, ui, uv)
+        torch.cuda.synchronize()
+        h = e.copy()
+        wi, wv = oracle.worker_stage(g, h, 1.0, K)
+        G.assert_same_bits(ui, wi, f"path {path} up_idx")
+        G.assert_same_bits(uv, wv, f"path {path} up_val")
+        G.assert_same_bits(te, h, f"path {path} eps")
+
+
 def test_threshold_far_above_the_sampled_bound_goes_to_the_dense_path(G, oracle):
     """The single-pass select works in a window of four octaves above its sampled lower
     bound.  Here 1.5 K spikes of magnitude 1e3..2e3 sit on N(0,1) noise: the sample puts
