@@ -31,21 +31,22 @@ def algorithmic_bytes(N, d, K_up, K_dn):
     return 12 * N * d + 4 * d + 24 * N * K_up + 20 * K_dn
 
 
-def cpu_baseline(cfg, g_first, budget_rows):
-    """The oracle's worker stage timed on a bounded sample: `budget_rows` worker rows of
-    the first step's gradients, one thread per row."""
+def cpu_baseline(cfg, g_first, threads):
+    """The oracle's worker stage timed on a bounded sample: two worker rows per thread of
+    the first step's gradients."""
     import numpy as np
     import oracle
-    rows = min(budget_rows, cfg.N)
+    threads = max(1, min(threads, cfg.N))
+    rows = min(2 * threads, cfg.N)
     g = g_first[:rows].cpu().numpy()
     eps = np.zeros_like(g)
     oracle.build()
     t0 = time.perf_counter()
-    oracle.worker_stage(g, eps, cfg.alpha, cfg.K_up, nthreads=rows)
+    oracle.worker_stage(g, eps, cfg.alpha, cfg.K_up, nthreads=threads)
     dt = time.perf_counter() - t0
-    return {"value": rows * cfg.d / dt, "unit": "coords/s", "cores": rows, "kind": "oracle",
+    return {"value": rows * cfg.d / dt, "unit": "coords/s", "cores": threads, "kind": "oracle",
             "sample": f"worker lines of Algorithm 2 (error compensation + full-sort Top_K) on "
-                      f"{rows} of {cfg.N} rows of {cfg.name} step 1, one thread per row, "
+                      f"{rows} of {cfg.N} rows of {cfg.name} step 1, {threads} threads, "
                       f"{dt:.1f} s; server stage not included"}
 
 
@@ -69,7 +70,9 @@ def main() -> int:
                     help="instead of the step: time plain read / copy / fma-stream kernels with "
                          "the dominant kernel's access shape over the workload's g and eps "
                          "buffers and print their rates (what the part sustains for each mix)")
-    ap.add_argument("--cpu-rows", type=int, default=0)
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="threads of the oracle's timed sample (0 = the cores this process may "
+                         "use, at most 16)")
     ap.add_argument("--algo", choices=["bidir", "unidir", "bidir_diag"], default="bidir",
                     help="bidir: Algorithm 2 (the headline); unidir: Algorithm 1, the paper's "
                          "baseline (no downlink compression, no server residual); bidir_diag: "
@@ -270,8 +273,8 @@ def main() -> int:
         out["diagnostics_last_step"] = {"rho": dg[0], "rho_hat": dg[1],
                                         "one_minus_gamma_max": dg[2], "nnz_fraction": dg[6]}
     if not args.no_cpu_baseline:
-        rows = args.cpu_rows or min(len(os.sched_getaffinity(0)), 16)
-        out["cpu_baseline"] = cpu_baseline(cfg, ring[0], rows)
+        threads = args.cpu_threads or min(len(os.sched_getaffinity(0)), 16)
+        out["cpu_baseline"] = cpu_baseline(cfg, ring[0], threads)
     print(json.dumps(out))
     return 0
 
