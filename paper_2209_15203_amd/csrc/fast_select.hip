@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void k_pick_bound(uint32_t* __restrict__ sh
 // run, and records (start of the run, length) in the row's chunk directory.  Chunks
 // without hits leave their directory entry alone (it is zero between calls).  The partial
 // chunks at the ends of a row load element by element and append the same way.
-static_assert(kUnroll <= 2, "the packed per-slice counts below hold two 16-bit fields");
+static_assert(kUnroll == 1 || kUnroll % 2 == 0, "slices are counted in pairs");
 
 // flags: bit 4u + j set = element j of the lane's slice u is a hit; v: the lane's values;
 // i0: index in the row of the lane's first element of slice 0 (modulo 2^32 for lanes that
@@ -164,23 +164,35 @@ __device__ __forceinline__ void append_run(uint32_t flags, const float (&v)[kUnr
                                            uint32_t i0, uint32_t* counter, uint2* list,
                                            uint32_t cap, uint2* dir_entry) {
   if (__ballot(flags != 0) == 0) return;
-  uint32_t mine = 0;                          // hits of slice u in bits 16u .. 16u + 15
+  // index order: slice 0 of every lane, then slice 1, ...  The hits of two slices are
+  // counted in the halves of one word (a slice has 256 elements: no carry) and scanned
+  // together.
+  constexpr int kPairs = (kUnroll + 1) / 2;
+  uint32_t excl[kPairs], tot[kPairs];
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u) mine |= (uint32_t)__popc((flags >> (4 * u)) & 0xFu) << (16 * u);
-  const uint32_t incl = wave_inclusive_scan(mine);          // a slice has 256 elements: no carry
-  const uint32_t tot = __shfl(incl, kWave - 1, kWave);
-  const uint32_t total = (tot & 0xFFFFu) + (tot >> 16);
+  for (int h = 0; h < kPairs; ++h) {
+    uint32_t mine = (uint32_t)__popc((flags >> (8 * h)) & 0xFu);
+    if (2 * h + 1 < kUnroll) mine |= (uint32_t)__popc((flags >> (8 * h + 4)) & 0xFu) << 16;
+    const uint32_t incl = wave_inclusive_scan(mine);
+    tot[h] = __shfl(incl, kWave - 1, kWave);
+    excl[h] = incl - mine;
+  }
+  uint32_t start[kUnroll];                    // hits in the slices before slice u
+  uint32_t total = 0;
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    start[u] = total;
+    total += (u & 1) ? (tot[u / 2] >> 16) : (tot[u / 2] & 0xFFFFu);
+  }
   uint32_t base = 0;
   if (lane_id() == 0) {
     base = atomicAdd(counter, total);
     *dir_entry = make_uint2(base, total);
   }
   base = __shfl(base, 0, kWave);
-  const uint32_t excl = incl - mine;
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
-    // index order: slice 0 of every lane, then slice 1
-    uint32_t pos = base + (u == 0 ? (excl & 0xFFFFu) : (tot & 0xFFFFu) + (excl >> 16));
+    uint32_t pos = base + start[u] + ((u & 1) ? (excl[u / 2] >> 16) : (excl[u / 2] & 0xFFFFu));
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (flags & (1u << (4 * u + j))) {
@@ -605,6 +617,15 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.stride = (uint32_t)stride;
   p.target = (uint32_t)target;
   p.cap = (uint32_t)cap;
+  // How many waves per compute unit the dense pass is held to (through LDS it requests and
+  // never touches): a stream of 2 reads : 1 write runs best well below full occupancy, but a
+  // wave whose chunk has hits waits for its append, and the more chunks have hits the more
+  // waves it takes to hide that.  About 3K candidates over d / kWaveChunk chunks.  Measured
+  // per launch: 13.3 against 13.7 ms at C5 (0.15 per chunk, 12 waves), 1.545 against 1.58 ms
+  // at C3 (1.5 per chunk, 20 waves; 12 waves: 1.67 ms), 0.342 against 0.346 ms at C2 (15
+  // per chunk, 26 waves).
+  const uint64_t per_chunk_x10 = 30ull * K * kWaveChunk / d;
+  p.stream_lds = per_chunk_x10 < 5 ? kMixedStreamLds : (per_chunk_x10 < 50 ? 16384u : 12288u);
   p.ntiles = (uint32_t)(((d + kWaveChunk - 1) / kWaveChunk + 1 + kTileChunks - 1) / kTileChunks);
   p.nwc_pad = p.ntiles * kTileChunks;
   return p;
@@ -642,7 +663,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   // the padded directory)
   if (ev0) (void)hipEventRecord(ev0, s);
   if (g != nullptr)
-    k_stream_capture<true><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
+    k_stream_capture<true><<<dense_grid, dim3(kStreamBlock), pl.stream_lds, s>>>(
         g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad);
   else
     k_stream_capture<false><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
