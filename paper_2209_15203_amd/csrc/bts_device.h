@@ -148,9 +148,12 @@ __device__ __forceinline__ ChunkGeom wave_chunk(uint64_t d, uint32_t row, uint32
 // lane with e = absolute offset of the lane's four consecutive elements, their values and
 // a 4-bit mask of those that belong to the row.  With FMA the visited value is
 // fma(alpha, g, x) and is stored back to x (each element by exactly one lane).
-template <bool FMA, typename F>
-__device__ __forceinline__ void visit_chunk(const float* __restrict__ g, float* __restrict__ x,
-                                            const ChunkGeom& c, float alpha, F&& f) {
+// streaming (uniform): x is read and written with non-temporal accesses -- the quicker way
+// when the rows are far larger than the caches (8.1 against 8.9 ms per dense step at N x d =
+// 1.6e9), the slower one when a row that is read again stays cached (rows of a few MB).
+template <bool FMA, bool STREAMING, typename F>
+__device__ __forceinline__ void visit_chunk_as(const float* __restrict__ g, float* __restrict__ x,
+                                               const ChunkGeom& c, float alpha, F&& f) {
   const uint64_t e0 = c.base + (uint64_t)lane_id() * 4;
   if (c.full) {
     f4 xv[kUnroll];
@@ -158,7 +161,8 @@ __device__ __forceinline__ void visit_chunk(const float* __restrict__ g, float* 
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint64_t e = e0 + (uint64_t)u * (kWave * 4);
-      xv[u] = *reinterpret_cast<const f4*>(x + e);
+      xv[u] = STREAMING ? __builtin_nontemporal_load(reinterpret_cast<const f4*>(x + e))
+                        : *reinterpret_cast<const f4*>(x + e);
       if (FMA) gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
     }
 #pragma unroll
@@ -169,7 +173,10 @@ __device__ __forceinline__ void visit_chunk(const float* __restrict__ g, float* 
         xv[u].y = __fmaf_rn(alpha, gv[u].y, xv[u].y);
         xv[u].z = __fmaf_rn(alpha, gv[u].z, xv[u].z);
         xv[u].w = __fmaf_rn(alpha, gv[u].w, xv[u].w);
-        *reinterpret_cast<f4*>(x + e) = xv[u];
+        if (STREAMING)
+          __builtin_nontemporal_store(xv[u], reinterpret_cast<f4*>(x + e));
+        else
+          *reinterpret_cast<f4*>(x + e) = xv[u];
       }
       const float v[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
       f(e, v, 0xFu);
@@ -197,6 +204,16 @@ __device__ __forceinline__ void visit_chunk(const float* __restrict__ g, float* 
       f(e, v, mask);
     }
   }
+}
+
+template <bool FMA, typename F>
+__device__ __forceinline__ void visit_chunk(const float* __restrict__ g, float* __restrict__ x,
+                                            const ChunkGeom& c, float alpha, bool streaming,
+                                            F&& f) {
+  if (streaming)
+    visit_chunk_as<FMA, true>(g, x, c, alpha, f);
+  else
+    visit_chunk_as<FMA, false>(g, x, c, alpha, f);
 }
 
 }  // namespace bts

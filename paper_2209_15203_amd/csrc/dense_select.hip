@@ -102,7 +102,7 @@ template <int DIGIT, bool FMA>
 __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
                                                  float* __restrict__ x, uint64_t d, float alpha,
                                                  uint32_t K, uint32_t* __restrict__ hist,
-                                                 uint32_t nwc, RowMask need) {
+                                                 uint32_t nwc, RowMask need, bool streaming) {
   constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
   __shared__ uint32_t sh[NB];
   __shared__ uint32_t lds[kBlock / kWave + 1];
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
        wc += gridDim.x * kWavesPerBlock) {
     const ChunkGeom c = wave_chunk(d, row, wc);
     if (!c.active) break;
-    visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t, const float (&v)[4], uint32_t mask) {
+    visit_chunk<FMA>(g, x, c, alpha, streaming, [&](uint64_t, const float (&v)[4], uint32_t mask) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (mask & (1u << j)) {
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, u
                                                   SelState* __restrict__ st,
                                                   uint32_t* __restrict__ cnt_gt,
                                                   uint32_t* __restrict__ cnt_eq, uint32_t nwc,
-                                                  RowMask need) {
+                                                  RowMask need, bool streaming) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
   const uint32_t row = blockIdx.y;
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, u
   const ChunkGeom c = wave_chunk(d, row, wc);
   uint32_t gt = 0, eq = 0;
   if (c.active) {
-    visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f,
+    visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f, streaming,
                        [&](uint64_t, const float (&v)[4], uint32_t mask) {
 #pragma unroll
                          for (int j = 0; j < 4; ++j) {
@@ -266,7 +266,8 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
                                                  const uint32_t* __restrict__ off_eq,
                                                  uint32_t nwc, uint32_t* __restrict__ out_idx,
                                                  float* __restrict__ out_val,
-                                                 uint32_t* __restrict__ hist, RowMask need) {
+                                                 uint32_t* __restrict__ hist, RowMask need,
+                                                 bool streaming) {
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
   if (blockIdx.x == 0)                             // leave the row's histograms clear
@@ -280,7 +281,8 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
   uint32_t run_eq = off_eq[(uint64_t)row * nwc + wc];
   uint32_t* oi = out_idx + (uint64_t)row * K;
   float* ov = out_val + (uint64_t)row * K;
-  visit_chunk<false>(nullptr, x, c, 0.0f, [&](uint64_t e, const float (&v)[4], uint32_t mask) {
+  visit_chunk<false>(nullptr, x, c, 0.0f, streaming,
+                     [&](uint64_t e, const float (&v)[4], uint32_t mask) {
     uint32_t fgt = 0, feq = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -319,7 +321,8 @@ __global__ __launch_bounds__(kBlock) void k_axpy(const float* __restrict__ g,
                                                  float alpha) {
   const uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
   const ChunkGeom c = wave_chunk(d, blockIdx.y, wc);
-  if (c.active) visit_chunk<true>(g, x, c, alpha, [](uint64_t, const float (&)[4], uint32_t) {});
+  if (c.active)
+    visit_chunk<true>(g, x, c, alpha, true, [](uint64_t, const float (&)[4], uint32_t) {});
 }
 
 __global__ void k_fill(uint32_t* p, uint64_t n, uint32_t v) {
@@ -377,6 +380,9 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   }
   const dim3 grid(gx, rows);
   const dim3 block(kBlock);
+  // rows that are read five times stay in the caches when they are small; beyond the 256 MB
+  // of last-level cache they are streamed past it
+  const bool streaming = (uint64_t)rows * d * 4 > (256ull << 20);
   if (*sc.dirty) {                                 // an earlier call failed half way
     hipError_t e = fill_u32(s, sc.hist, (uint64_t)rows_alloc * kRowHist, 0);
     if (e != hipSuccess) return e;
@@ -386,18 +392,19 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   const bool fuse = (g != nullptr) && !first_pass_done;
   if (fuse) {
     if (ev0) (void)hipEventRecord(ev0, s);
-    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, K, sc.hist, nwc, need);
+    k_hist<0, true><<<grid, block, 0, s>>>(g, x, d, alpha, K, sc.hist, nwc, need, streaming);
     BTS_LAUNCH_CHECK();
     if (ev1) (void)hipEventRecord(ev1, s);
   } else {
-    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need);
+    k_hist<0, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need, streaming);
     BTS_LAUNCH_CHECK();
   }
-  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need);
+  k_hist<1, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need, streaming);
   BTS_LAUNCH_CHECK();
-  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need);
+  k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need, streaming);
   BTS_LAUNCH_CHECK();
-  k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need);
+  k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need,
+                                 streaming);
   BTS_LAUNCH_CHECK();
   const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
   if (ntiles > 1) {                                // a single tile starts from zero
@@ -409,7 +416,7 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
                                                           sc.tile_sums, need);
   BTS_LAUNCH_CHECK();
   k_emit<<<grid, block, 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, out_idx, out_val,
-                                sc.hist, need);
+                                sc.hist, need, streaming);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   return hipSuccess;

@@ -250,7 +250,7 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
     }
   } else {
     int u = 0;
-    visit_chunk<FMA>(g, x, c, alpha, [&](uint64_t, const float (&vv)[4], uint32_t mask) {
+    visit_chunk<FMA>(g, x, c, alpha, false, [&](uint64_t, const float (&vv)[4], uint32_t mask) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         v[u][j] = vv[j];
