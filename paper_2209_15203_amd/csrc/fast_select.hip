@@ -80,8 +80,8 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(
       ok[u] = s0 + u < n_samp;
       const uint64_t e = (first + (s0 + u) * stride) * kSlice + (uint64_t)lane_id() * 4;
       if (ok[u]) {
-        xv[u] = *reinterpret_cast<const f4*>(x + e);
-        if (FMA) gv[u] = *reinterpret_cast<const f4*>(g + e);
+        xv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(x + e));
+        if (FMA) gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
       }
     }
 #pragma unroll
