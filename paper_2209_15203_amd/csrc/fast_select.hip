@@ -603,14 +603,25 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   // single-pass ahead from 25.5 M on).
   p.preferred = (uint64_t)rows * d >= 25000000ull;
   const uint64_t slices = d / 256;
-  uint64_t stride = K / 64;        // about 128 of the sampled coordinates fall in the top 2K
+  // Every stride-th slice is sampled: 64 / K of the row, which puts 64 sampled coordinates
+  // in the row's top K, or 1 / 171 of the row where that is more (a sample of that size is
+  // still bound by the launch, not by its reads, up to rows of about 3e7).
+  uint64_t stride = K / 64;
+  if (stride > 171) stride = 171;
   if (stride < 16) stride = 16;
-  if (stride > 4096) stride = 4096;
   if (stride > slices / 64) stride = slices / 64;
   if (stride < 1) stride = 1;
-  uint64_t target = (2ull * K + stride - 1) / stride;
+  // The bound aims at the rank M = K (1 + 7 / sqrt(h)), h = K / stride the sampled
+  // coordinates expected in the top K: seven binomial standard deviations above K, between
+  // 1.15 K and 2 K.
+  const double h = (double)K / (double)stride;
+  double over = 7.0 / __builtin_sqrt(h > 1.0 ? h : 1.0);
+  if (over > 1.0) over = 1.0;
+  if (over < 0.15) over = 0.15;
+  const uint64_t M = (uint64_t)((double)K * (1.0 + over)) + 1;
+  uint64_t target = (M + stride - 1) / stride;
   if (target < 48) target = 48;
-  // expected list length is 2K..4K (the bound is a histogram bin edge); each of the 64
+  // expected list length is M..2M (the bound is a histogram bin edge); each of the 64
   // lists gets twice its even share of 4x the target plus slack
   uint64_t cap = (4 * target * stride + 4096) / 64 * 2 + 64;
   p.enabled = true;
