@@ -6,7 +6,8 @@
 //
 //   1. sample:   a strided sample (256-coordinate slices, every S-th slice) of a = eps +
 //                alpha g is histogrammed on the top 13 bits of the magnitude key; a lower
-//                bound L is chosen so that about 2K coordinates of the row lie at or above it.
+//                bound L is chosen so that between 1.15 K and 2 K coordinates of the row (by
+//                the sample's size) are expected at or above it.
 //   2. stream:   the one dense pass computes a, stores it over eps and appends every
 //                coordinate with key >= L to the row's candidate lists: the hits of a wave
 //                chunk (512 coordinates) go, in index order, into one run of one list (one
