@@ -599,10 +599,11 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.enabled = false;
   p.preferred = false;
   if (K == 0 || d < (1ull << 16) || (uint64_t)K * 64 > d) return p;
-  // Below about 25 M coordinates per call the step is bound by kernel launches and the
-  // dense path, with fewer launches, is the quicker one (measured: dense ahead at 24 M,
-  // single-pass ahead from 25.5 M on).
-  p.preferred = (uint64_t)rows * d >= 25000000ull;
+  // Small calls are bound by kernel launches and the dense path, with fewer launches, is
+  // the quicker one.  Measured crossovers: 1.1e7 coordinates per call for several rows (at
+  // 1.2e7 the single pass is 8 % ahead, at 2.4e7 21 %; at 8e6 the dense path is 6 % ahead),
+  // 2.5e7 for a single row, which the dense path spreads over the chip just as well.
+  p.preferred = rows == 1 ? d >= 25000000ull : (uint64_t)rows * d >= 11000000ull;
   const uint64_t slices = d / 256;
   // Every stride-th slice is sampled: 64 / K of the row, which puts 64 sampled coordinates
   // in the row's top K, or 1 / 171 of the row where that is more (a sample of that size is
