@@ -186,9 +186,10 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
 
 /* Testing aid: which select path later calls on this context take.  0 (default): chosen
  * by shape (one workgroup per row up to d = 8192, else dense multi-pass, else single-pass
- * from about 1.1e7 coordinates per call, 2.5e7 for a single row); 1: the dense multi-pass path only (the path that
- * also serves as the fallback); 2: the single-pass path wherever the shape allows it
- * (d >= 65536 and K <= d/64), whatever its size.  Results are identical in every mode. */
+ * from about 1.1e7 coordinates per call, 2.5e7 for a single row); 1: the dense multi-pass
+ * path only (the path that also serves as the fallback); 2: the single-pass path wherever
+ * the shape allows it (d >= 65536 and K <= d/64), whatever its size.  Results are identical
+ * in every mode. */
 int bts_set_path(bts_ctx* ctx, int mode);
 
 #ifdef __cplusplus
