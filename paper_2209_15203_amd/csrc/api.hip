@@ -149,10 +149,8 @@ int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha,
   } else if (ctx->path_mode == 0 && row_select_fits(ctx->d)) {
     e = row_select(ctx->stream, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
   } else if (use_fast(ctx, pl)) {
-    e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
-    if (e == hipSuccess)
-      e = dense_select(ctx->stream, ctx->dense, nullptr, x, rows, ctx->d, K, 0.0f, idx, val,
-                       fs.need, true, nullptr, nullptr);
+    e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1,
+                    ctx->dense);
   } else {
     e = dense_select(ctx->stream, ctx->dense, g, x, rows, ctx->d, K, alpha, idx, val, nullptr,
                      false, e0, e1);

@@ -60,6 +60,20 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
                         float* out_val, RowMask need, bool first_pass_done,
                         hipEvent_t ev0, hipEvent_t ev1);
 
+// The pieces of dense_select for a caller that runs the first four kernels (three digit
+// histograms and the per-chunk counts, see dense_bodies.h) inside launches of its own:
+// dense_begin before them, dense_finish (scan of the counts and emission) after them.
+struct DensePlan {
+  uint32_t nwc;        // wave chunks per row
+  uint32_t gx;         // blocks in x of the looping kernels
+  bool streaming;      // read x past the caches
+};
+DensePlan dense_plan(const DenseScratch& sc, uint32_t rows, uint64_t d);
+hipError_t dense_begin(hipStream_t s, const DenseScratch& sc);
+hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
+                        uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
+                        float* out_val, RowMask need);
+
 // x = fma(alpha, g, x) over rows x d and nothing else (K == 0).
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
                      float alpha, hipEvent_t ev0, hipEvent_t ev1);
@@ -103,11 +117,14 @@ size_t fast_sel_bytes();
 uint32_t fast_sublists();
 uint32_t fast_counter_stride();
 size_t fast_hist_words();
-// Same contract as dense_select, except that rows whose need flag is set on return are
-// left unselected (x already holds fma(alpha, g, x) for every row).
+// Same contract as dense_select.  Rows that the single pass cannot finish are flagged and
+// redone by the dense path inside this call (its first four kernels share launches with the
+// tail of the single-pass select, the rest follows); x holds fma(alpha, g, x) for every row
+// before the redo starts.
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
-                       uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1);
+                       uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
+                       const DenseScratch& dense);
 
 // ---- server side ------------------------------------------------------------------------
 uint32_t aggregate_ranges(uint64_t d);

@@ -11,189 +11,29 @@
 // delta_t = g_t - Top_K(g_t)); the first pass can also fuse the worker's error
 // compensation a^q = eps^q + alpha g^q.
 
-#include "bts_device.h"
+#include "dense_bodies.h"
 
 namespace bts {
 
 namespace {
 
-__device__ __forceinline__ bool row_needed(RowMask need, uint32_t row) {
-  return need == nullptr || need[row] != 0;
-}
-
-// Each row has three global histograms (digit 0: 2048 bins, digits 1 and 2: 1024 bins), all
-// zero between calls.  A kernel that needs the digits found so far walks the finished
-// histograms itself at its start (every block, redundantly: a few thousand loads), which
-// saves a separate launch per digit.
-constexpr int kRowHist = kBins0 + 2 * kBinsLo;     // words of histogram per row
-
-// Walk an NB-bin histogram from the top bin down and find the bin holding the `want`-th
-// largest key; *above = keys in higher bins.  All threads of the block call this; the result
-// is returned to every thread.
-template <int NB>
-__device__ __forceinline__ uint32_t resolve_digit(const uint32_t* __restrict__ h, uint32_t want,
-                                                  uint32_t* lds, uint32_t* s_out,
-                                                  uint32_t* above) {
-  constexpr int BPT = NB / kBlock;
-  const int top = NB - 1 - (int)threadIdx.x * BPT;   // this thread's highest bin
-  uint32_t c[BPT];
-  uint32_t s = 0;
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) {
-    c[i] = h[top - i];
-    s += c[i];
-  }
-  uint32_t total;
-  const uint32_t excl = block_exclusive_scan(s, lds, &total);   // count in higher bins
-  if (excl < want && want <= excl + s) {                         // exactly one thread
-    uint32_t acc = excl;
-    int bin = top;
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) {
-      if (acc + c[i] >= want) {
-        bin = top - i;
-        break;
-      }
-      acc += c[i];
-    }
-    s_out[0] = (uint32_t)bin;
-    s_out[1] = acc;
-  }
-  __syncthreads();
-  const uint32_t bin = s_out[0];
-  *above = s_out[1];
-  __syncthreads();
-  return bin;
-}
-
-// The digits fixed by the finished histograms of the row: after `digits` of them the key
-// prefix (right aligned) and how many of the K wanted keys lie at or below the prefix's bin.
-struct Resolved {
-  uint32_t prefix, k_rem;
-};
-
-template <int DIGITS>
-__device__ __forceinline__ Resolved resolve_row(const uint32_t* __restrict__ hist_row, uint32_t K,
-                                                uint32_t* lds, uint32_t* s_out) {
-  Resolved r{0u, K};
-  uint32_t above;
-  if (DIGITS >= 1) {
-    const uint32_t b = resolve_digit<kBins0>(hist_row, r.k_rem, lds, s_out, &above);
-    r.prefix = b;
-    r.k_rem -= above;
-  }
-  if (DIGITS >= 2) {
-    const uint32_t b = resolve_digit<kBinsLo>(hist_row + kBins0, r.k_rem, lds, s_out, &above);
-    r.prefix = (r.prefix << 10) | b;
-    r.k_rem -= above;
-  }
-  if (DIGITS >= 3) {
-    const uint32_t b =
-        resolve_digit<kBinsLo>(hist_row + kBins0 + kBinsLo, r.k_rem, lds, s_out, &above);
-    r.prefix = (r.prefix << 10) | b;      // the exact K-th largest key T
-    r.k_rem -= above;                     // how many holders of T are kept
-  }
-  return r;
-}
-
-// Histogram of one digit of the key over every coordinate of the row whose higher digits
-// match the prefix found so far.
 template <int DIGIT, bool FMA>
 __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
                                                  float* __restrict__ x, uint64_t d, float alpha,
                                                  uint32_t K, uint32_t* __restrict__ hist,
                                                  uint32_t nwc, RowMask need, bool streaming) {
-  constexpr int NB = DIGIT == 0 ? kBins0 : kBinsLo;
-  __shared__ uint32_t sh[NB];
-  __shared__ uint32_t lds[kBlock / kWave + 1];
-  __shared__ uint32_t s_out[2];
-  const uint32_t row = blockIdx.y;
-  if (!row_needed(need, row)) return;
-  uint32_t* hist_row = hist + (uint64_t)row * kRowHist;
-  for (int i = threadIdx.x; i < NB; i += kBlock) sh[i] = 0;
-  const uint32_t prefix = resolve_row<DIGIT>(hist_row, K, lds, s_out).prefix;
-  __syncthreads();
-  // Bin 0 is counted per lane: a sparse row (the server's g_t is mostly exact zeros) would
-  // otherwise serialise the whole wave on one LDS address.
-  uint32_t bin0 = 0;
-  for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
-       wc += gridDim.x * kWavesPerBlock) {
-    const ChunkGeom c = wave_chunk(d, row, wc);
-    if (!c.active) break;
-    visit_chunk<FMA>(g, x, c, alpha, streaming, [&](uint64_t, const float (&v)[4], uint32_t mask) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (mask & (1u << j)) {
-          const uint32_t key = key_of(v[j]);
-          uint32_t bin;
-          bool hit;
-          if (DIGIT == 0) {
-            bin = key >> 20;
-            hit = true;
-          } else if (DIGIT == 1) {
-            bin = (key >> 10) & 1023u;
-            hit = (key >> 20) == prefix;
-          } else {
-            bin = key & 1023u;
-            hit = (key >> 10) == prefix;
-          }
-          if (hit) {
-            if (bin == 0) ++bin0; else atomicAdd(&sh[bin], 1u);
-          }
-        }
-      }
-    });
-  }
-  if (bin0) atomicAdd(&sh[0], bin0);
-  __syncthreads();
-  uint32_t* h = hist_row + (DIGIT == 0 ? 0 : (DIGIT == 1 ? kBins0 : kBins0 + kBinsLo));
-  for (int i = threadIdx.x; i < NB; i += kBlock) {
-    const uint32_t v = sh[i];
-    if (v) atomicAdd(&h[i], v);
-  }
+  hist_body<DIGIT, FMA>(VGrid{blockIdx.x, blockIdx.y, gridDim.x}, g, x, d, alpha, K, hist, nwc,
+                        need, streaming);
 }
 
-// Per wave-chunk: how many coordinates lie strictly above the threshold key, how many
-// on it.
 __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, uint64_t d,
                                                   uint32_t K, const uint32_t* __restrict__ hist,
                                                   SelState* __restrict__ st,
                                                   uint32_t* __restrict__ cnt_gt,
                                                   uint32_t* __restrict__ cnt_eq, uint32_t nwc,
                                                   RowMask need, bool streaming) {
-  __shared__ uint32_t lds[kBlock / kWave + 1];
-  __shared__ uint32_t s_out[2];
-  const uint32_t row = blockIdx.y;
-  if (!row_needed(need, row)) return;
-  const Resolved res = resolve_row<3>(hist + (uint64_t)row * kRowHist, K, lds, s_out);
-  const uint32_t T = res.prefix;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {       // for the emission kernel
-    st[row].T = T;
-    st[row].r = res.k_rem;
-  }
-  for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
-       wc += gridDim.x * kWavesPerBlock) {
-  const ChunkGeom c = wave_chunk(d, row, wc);
-  uint32_t gt = 0, eq = 0;
-  if (c.active) {
-    visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f, streaming,
-                       [&](uint64_t, const float (&v)[4], uint32_t mask) {
-#pragma unroll
-                         for (int j = 0; j < 4; ++j) {
-                           const uint32_t key = key_of(v[j]);
-                           const bool in = mask & (1u << j);
-                           gt += (in && key > T) ? 1u : 0u;
-                           eq += (in && key == T) ? 1u : 0u;
-                         }
-                       });
-  }
-  gt = wave_sum(gt);
-  eq = wave_sum(eq);
-  if (lane_id() == 0) {
-    cnt_gt[(uint64_t)row * nwc + wc] = gt;
-    cnt_eq[(uint64_t)row * nwc + wc] = eq;
-  }
-  }
+  count_body(VGrid{blockIdx.x, blockIdx.y, gridDim.x}, x, d, K, hist, st, cnt_gt, cnt_eq, nwc,
+             need, streaming);
 }
 
 // Exclusive scan of the per-chunk counts of every row, in place, in two levels: sums of
@@ -359,36 +199,68 @@ hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uin
 
 uint32_t dense_row_hist_words() { return kRowHist; }
 
-hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
-                        uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
-                        float* out_val, RowMask need, bool first_pass_done,
-                        hipEvent_t ev0, hipEvent_t ev1) {
-  const uint32_t rows_alloc = sc.rows;
-  const uint32_t nwc = sc.nwc;
+DensePlan dense_plan(const DenseScratch& sc, uint32_t rows, uint64_t d) {
+  DensePlan pl;
+  pl.nwc = sc.nwc;
   // A bounded grid whose blocks loop over the chunks: every block flushes its LDS histogram
   // to the row's global histogram with atomics that are served at the memory side and
   // serialise per address, so few fat blocks beat many thin ones; and as a gated fallback
   // most rows leave at once, which keeps idle launches cheap.
-  uint32_t gx = (nwc + kWavesPerBlock - 1) / kWavesPerBlock;
-  {
-    // at least 256 blocks per row, so that a lone row that falls back still streams fast;
-    // a single row gets 512 (measured at d = 1.1e7: 512 blocks beat 256 by their streaming,
-    // 2048 and 4096 lose 40 and 120 us per select to the flush into the row's histogram)
-    uint32_t lim = 512u / rows;
-    if (lim < 256u) lim = 256u;
-    if (gx > lim) gx = lim;
-  }
-  const dim3 grid(gx, rows);
-  const dim3 block(kBlock);
+  uint32_t gx = (pl.nwc + kWavesPerBlock - 1) / kWavesPerBlock;
+  // at least 256 blocks per row, so that a lone row that falls back still streams fast;
+  // a single row gets 512 (measured at d = 1.1e7: 512 blocks beat 256 by their streaming,
+  // 2048 and 4096 lose 40 and 120 us per select to the flush into the row's histogram)
+  uint32_t lim = 512u / rows;
+  if (lim < 256u) lim = 256u;
+  if (gx > lim) gx = lim;
+  pl.gx = gx;
   // rows that are read five times stay in the caches when they are small; beyond the 256 MB
   // of last-level cache they are streamed past it
-  const bool streaming = (uint64_t)rows * d * 4 > (256ull << 20);
+  pl.streaming = (uint64_t)rows * d * 4 > (256ull << 20);
+  return pl;
+}
+
+hipError_t dense_begin(hipStream_t s, const DenseScratch& sc) {
   if (*sc.dirty) {                                 // an earlier call failed half way
-    hipError_t e = fill_u32(s, sc.hist, (uint64_t)rows_alloc * kRowHist, 0);
+    hipError_t e = fill_u32(s, sc.hist, (uint64_t)sc.rows * kRowHist, 0);
     if (e != hipSuccess) return e;
   }
   *sc.dirty = true;                                // cleared when every launch went out
+  return hipSuccess;
+}
 
+hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
+                        uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
+                        float* out_val, RowMask need) {
+  const uint32_t nwc = pl.nwc;
+  const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
+  if (ntiles > 1) {                                // a single tile starts from zero
+    k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
+                                                          sc.tile_sums, need);
+    BTS_LAUNCH_CHECK();
+  }
+  k_scan_chunks<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
+                                                          sc.tile_sums, need);
+  BTS_LAUNCH_CHECK();
+  k_emit<<<dim3(pl.gx, rows), dim3(kBlock), 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc,
+                                                    out_idx, out_val, sc.hist, need,
+                                                    pl.streaming);
+  BTS_LAUNCH_CHECK();
+  *sc.dirty = false;
+  return hipSuccess;
+}
+
+hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
+                        uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
+                        float* out_val, RowMask need, bool first_pass_done,
+                        hipEvent_t ev0, hipEvent_t ev1) {
+  const DensePlan pl = dense_plan(sc, rows, d);
+  const uint32_t nwc = pl.nwc;
+  const bool streaming = pl.streaming;
+  const dim3 grid(pl.gx, rows);
+  const dim3 block(kBlock);
+  hipError_t e = dense_begin(s, sc);
+  if (e != hipSuccess) return e;
   const bool fuse = (g != nullptr) && !first_pass_done;
   if (fuse) {
     if (ev0) (void)hipEventRecord(ev0, s);
@@ -406,20 +278,7 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need,
                                  streaming);
   BTS_LAUNCH_CHECK();
-  const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
-  if (ntiles > 1) {                                // a single tile starts from zero
-    k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
-                                                          sc.tile_sums, need);
-    BTS_LAUNCH_CHECK();
-  }
-  k_scan_chunks<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
-                                                          sc.tile_sums, need);
-  BTS_LAUNCH_CHECK();
-  k_emit<<<grid, block, 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, out_idx, out_val,
-                                sc.hist, need, streaming);
-  BTS_LAUNCH_CHECK();
-  *sc.dirty = false;
-  return hipSuccess;
+  return dense_finish(s, sc, pl, x, rows, d, K, out_idx, out_val, need);
 }
 
 }  // namespace bts

@@ -36,7 +36,7 @@
 // wave chunk, per-block partial histograms with plain stores, kernel boundaries instead of
 // last-block-done tickets, and an emission that needs no atomics at all.
 
-#include "bts_device.h"
+#include "dense_bodies.h"
 
 namespace bts {
 
@@ -367,14 +367,14 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) out[i] = sh[i];
 }
 
-__global__ __launch_bounds__(kBlock) void k_cand_finish(const uint32_t* __restrict__ partial,
-                                                        uint32_t nparts,
-                                                        const uint32_t* __restrict__ lower_key,
-                                                        FastSel* __restrict__ sel,
-                                                        const uint32_t* __restrict__ need) {
+__device__ __forceinline__ void cand_finish_body(uint32_t row,
+                                                 const uint32_t* __restrict__ partial,
+                                                 uint32_t nparts,
+                                                 const uint32_t* __restrict__ lower_key,
+                                                 FastSel* __restrict__ sel,
+                                                 const uint32_t* __restrict__ need) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
-  const uint32_t row = blockIdx.x;
   if (need[row]) return;
   const FastSel s = sel[row];
   uint32_t above;
@@ -443,16 +443,16 @@ __device__ __forceinline__ uint2 tile_entry(const TileView& t, uint32_t e,
 }
 
 template <int TPW>
-__global__ __launch_bounds__(kBlock) void k_dir_count(
-    const uint2* __restrict__ dir, uint32_t nwc_pad, const uint2* __restrict__ cand,
-    uint32_t cap, const FastSel* __restrict__ sel, const uint32_t* __restrict__ need,
-    unsigned long long* __restrict__ tile_cnt, uint32_t ntiles) {
+__device__ __forceinline__ void dir_count_body(
+    uint32_t bx, uint32_t row, const uint2* __restrict__ dir, uint32_t nwc_pad,
+    const uint2* __restrict__ cand, uint32_t cap, const FastSel* __restrict__ sel,
+    const uint32_t* __restrict__ need, unsigned long long* __restrict__ tile_cnt,
+    uint32_t ntiles) {
   __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
-  const uint32_t row = blockIdx.y;
   if (need[row]) return;
   const uint32_t w = threadIdx.x / kWave;
   const uint32_t quarter = (ntiles + TPW - 1) / TPW;
-  const uint32_t v = blockIdx.x * kWavesPerBlock + w;
+  const uint32_t v = bx * kWavesPerBlock + w;
   if (v >= quarter) return;
   const uint2* dir_row = dir + (uint64_t)row * nwc_pad;
   uint2 ent[TPW];
@@ -493,11 +493,11 @@ __global__ __launch_bounds__(kBlock) void k_dir_count(
 }
 
 // One block per row; every thread owns a contiguous share of the tiles.
-__global__ __launch_bounds__(kBlock) void k_dir_scan(unsigned long long* __restrict__ tile_cnt,
-                                                     uint32_t ntiles,
-                                                     const uint32_t* __restrict__ need) {
+__device__ __forceinline__ void dir_scan_body(uint32_t row,
+                                              unsigned long long* __restrict__ tile_cnt,
+                                              uint32_t ntiles,
+                                              const uint32_t* __restrict__ need) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
-  const uint32_t row = blockIdx.x;
   if (need[row]) return;
   unsigned long long* tc = tile_cnt + (uint64_t)row * ntiles;
   const uint32_t per = (ntiles + kBlock - 1) / kBlock;
@@ -520,16 +520,16 @@ __global__ __launch_bounds__(kBlock) void k_dir_scan(unsigned long long* __restr
 }
 
 template <int TPW>
-__global__ __launch_bounds__(kBlock) void k_dir_emit(
-    uint2* __restrict__ dir, uint32_t nwc_pad, const uint2* __restrict__ cand, uint32_t cap,
-    const FastSel* __restrict__ sel, const uint32_t* __restrict__ need,
-    const unsigned long long* __restrict__ tile_cnt, uint32_t ntiles, float* __restrict__ x,
-    uint64_t d, uint32_t K, uint32_t* __restrict__ out_idx, float* __restrict__ out_val) {
+__device__ __forceinline__ void dir_emit_body(
+    uint32_t bx, uint32_t row, uint2* __restrict__ dir, uint32_t nwc_pad,
+    const uint2* __restrict__ cand, uint32_t cap, const FastSel* __restrict__ sel,
+    const uint32_t* __restrict__ need, const unsigned long long* __restrict__ tile_cnt,
+    uint32_t ntiles, float* __restrict__ x, uint64_t d, uint32_t K,
+    uint32_t* __restrict__ out_idx, float* __restrict__ out_val) {
   __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
-  const uint32_t row = blockIdx.y;
   const uint32_t w = threadIdx.x / kWave;
   const uint32_t quarter = (ntiles + TPW - 1) / TPW;
-  const uint32_t v = blockIdx.x * kWavesPerBlock + w;
+  const uint32_t v = bx * kWavesPerBlock + w;
   if (v >= quarter) return;
   uint2* dir_row = dir + (uint64_t)row * nwc_pad;
   uint2 ent[TPW];
@@ -584,6 +584,77 @@ __global__ __launch_bounds__(kBlock) void k_dir_emit(
       }
     }
   }
+}
+
+// ---- the tail of the select and the gated dense redo in the same launches -----------------
+// The rows' flags are final once k_cand_hist1 has run.  The four kernels that remain of the
+// single-pass select and the first four of the dense redo of the flagged rows (idle unless
+// a row is flagged, but a launch costs 4-5 us either way) do not depend on each other, so
+// each pair shares a launch: the first `own` workgroups of the 1-D grid do the select's
+// part, the others the dense part on a virtual (gx, rows) grid.  The rest of the redo
+// (scan of the counts, emission) follows in launches of its own.
+struct DensePart {
+  float* x;
+  uint64_t d;
+  uint32_t K;
+  uint32_t* hist;
+  SelState* state;
+  uint32_t* cnt_gt;
+  uint32_t* cnt_eq;
+  uint32_t nwc, gx;
+  bool streaming;
+};
+
+__device__ __forceinline__ VGrid dense_vgrid(uint32_t b, const DensePart& dp) {
+  return VGrid{b % dp.gx, b / dp.gx, dp.gx};
+}
+
+__global__ __launch_bounds__(kBlock) void k_finish_hist0(uint32_t own, const uint32_t* partial,
+                                                         uint32_t nparts,
+                                                         const uint32_t* lower_key, FastSel* sel,
+                                                         const uint32_t* need, DensePart dp) {
+  if (blockIdx.x < own)
+    cand_finish_body(blockIdx.x, partial, nparts, lower_key, sel, need);
+  else
+    hist_body<0, false>(dense_vgrid(blockIdx.x - own, dp), nullptr, dp.x, dp.d, 0.0f, dp.K,
+                        dp.hist, dp.nwc, need, dp.streaming);
+}
+
+template <int TPW>
+__global__ __launch_bounds__(kBlock) void k_dircount_hist1(
+    uint32_t own, uint32_t own_gx, const uint2* dir, uint32_t nwc_pad, const uint2* cand,
+    uint32_t cap, const FastSel* sel, const uint32_t* need, unsigned long long* tile_cnt,
+    uint32_t ntiles, DensePart dp) {
+  if (blockIdx.x < own)
+    dir_count_body<TPW>(blockIdx.x % own_gx, blockIdx.x / own_gx, dir, nwc_pad, cand, cap, sel,
+                        need, tile_cnt, ntiles);
+  else
+    hist_body<1, false>(dense_vgrid(blockIdx.x - own, dp), nullptr, dp.x, dp.d, 0.0f, dp.K,
+                        dp.hist, dp.nwc, need, dp.streaming);
+}
+
+__global__ __launch_bounds__(kBlock) void k_dirscan_hist2(uint32_t own,
+                                                          unsigned long long* tile_cnt,
+                                                          uint32_t ntiles, const uint32_t* need,
+                                                          DensePart dp) {
+  if (blockIdx.x < own)
+    dir_scan_body(blockIdx.x, tile_cnt, ntiles, need);
+  else
+    hist_body<2, false>(dense_vgrid(blockIdx.x - own, dp), nullptr, dp.x, dp.d, 0.0f, dp.K,
+                        dp.hist, dp.nwc, need, dp.streaming);
+}
+
+template <int TPW>
+__global__ __launch_bounds__(kBlock) void k_diremit_count(
+    uint32_t own, uint32_t own_gx, uint2* dir, uint32_t nwc_pad, const uint2* cand, uint32_t cap,
+    const FastSel* sel, const uint32_t* need, const unsigned long long* tile_cnt,
+    uint32_t ntiles, uint32_t* out_idx, float* out_val, DensePart dp) {
+  if (blockIdx.x < own)
+    dir_emit_body<TPW>(blockIdx.x % own_gx, blockIdx.x / own_gx, dir, nwc_pad, cand, cap, sel,
+                       need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val);
+  else
+    count_body(dense_vgrid(blockIdx.x - own, dp), dp.x, dp.d, dp.K, dp.hist, dp.state,
+               dp.cnt_gt, dp.cnt_eq, dp.nwc, need, dp.streaming);
 }
 
 #define BTS_LAUNCH_CHECK()                       \
@@ -646,7 +717,8 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
 
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
-                       uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1) {
+                       uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
+                       const DenseScratch& dense) {
   const dim3 block(kBlock);
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
   const dim3 dense_grid((nwc + kStreamWaves - 1) / kStreamWaves, rows);
@@ -696,30 +768,54 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
                                                   sc.hist, sel, sc.need);
   BTS_LAUNCH_CHECK();
-  k_cand_finish<<<dim3(rows), block, 0, s>>>(sc.hist, hb, sc.lower_key, sel, sc.need);
-  BTS_LAUNCH_CHECK();
-  // 5. emit
+  // 4 (rest) + 5 + the first four kernels of the gated dense redo, pair by pair
+  const DensePlan dpl = dense_plan(dense, rows, d);
+  hipError_t e = dense_begin(s, dense);
+  if (e != hipSuccess) return e;
+  DensePart dp;
+  dp.x = x;
+  dp.d = d;
+  dp.K = K;
+  dp.hist = dense.hist;
+  dp.state = dense.state;
+  dp.cnt_gt = dense.cnt_gt;
+  dp.cnt_eq = dense.cnt_eq;
+  dp.nwc = dpl.nwc;
+  dp.gx = dpl.gx;
+  dp.streaming = dpl.streaming;
+  const uint64_t dense_blocks = (uint64_t)dpl.gx * rows;
   const bool sparse_tiles = 3ull * K < 16ull * pl.ntiles;      // under 16 candidates per tile
   const uint32_t tile_waves = sparse_tiles ? (pl.ntiles + 3) / 4 : pl.ntiles;
-  const dim3 tgrid((tile_waves + kWavesPerBlock - 1) / kWavesPerBlock, rows);
-  if (sparse_tiles)
-    k_dir_count<4><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                           tile_cnt, pl.ntiles);
-  else
-    k_dir_count<1><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                           tile_cnt, pl.ntiles);
-  BTS_LAUNCH_CHECK();
-  k_dir_scan<<<dim3(rows), block, 0, s>>>(tile_cnt, pl.ntiles, sc.need);
+  const uint32_t tgx = (tile_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  const uint64_t tile_blocks = (uint64_t)tgx * rows;
+  if (tile_blocks + dense_blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  const dim3 grid_rows((unsigned)(rows + dense_blocks));
+  const dim3 grid_tiles((unsigned)(tile_blocks + dense_blocks));
+  k_finish_hist0<<<grid_rows, block, 0, s>>>(rows, sc.hist, hb, sc.lower_key, sel, sc.need, dp);
   BTS_LAUNCH_CHECK();
   if (sparse_tiles)
-    k_dir_emit<4><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                          tile_cnt, pl.ntiles, x, d, K, out_idx, out_val);
+    k_dircount_hist1<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
+                                                     pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                                     tile_cnt, pl.ntiles, dp);
   else
-    k_dir_emit<1><<<tgrid, block, 0, s>>>(sc.dir, pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                          tile_cnt, pl.ntiles, x, d, K, out_idx, out_val);
+    k_dircount_hist1<1><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
+                                                     pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                                     tile_cnt, pl.ntiles, dp);
+  BTS_LAUNCH_CHECK();
+  k_dirscan_hist2<<<grid_rows, block, 0, s>>>(rows, tile_cnt, pl.ntiles, sc.need, dp);
+  BTS_LAUNCH_CHECK();
+  if (sparse_tiles)
+    k_diremit_count<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
+                                                    pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                                    tile_cnt, pl.ntiles, out_idx, out_val, dp);
+  else
+    k_diremit_count<1><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
+                                                    pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                                    tile_cnt, pl.ntiles, out_idx, out_val, dp);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
-  return hipSuccess;
+  // the rest of the redo: scan of the per-chunk counts, emission of the flagged rows
+  return dense_finish(s, dense, dpl, x, rows, d, K, out_idx, out_val, sc.need);
 }
 
 size_t fast_sel_bytes() { return sizeof(FastSel); }
