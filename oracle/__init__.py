@@ -33,6 +33,19 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """Compile the oracle together with sanitize_driver.cpp into one executable under
+    AddressSanitizer and UndefinedBehaviorSanitizer (host code only) and return its path.
+    The runtimes are linked statically so that a preloaded library cannot come before them."""
+    exe = os.path.join(_HERE, "oracle_sanitized")
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-ffp-contract=off", "-fno-fast-math",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-static-libasan", "-static-libubsan", "-pthread", "-o", exe, _SRC,
+           os.path.join(_HERE, "sanitize_driver.cpp")]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 def _load():
     global _lib
     if _lib is not None:
