@@ -31,23 +31,128 @@ def algorithmic_bytes(N, d, K_up, K_dn):
     return 12 * N * d + 4 * d + 24 * N * K_up + 20 * K_dn
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, g_first, threads):
-    """The oracle's worker stage timed on a bounded sample: two worker rows per thread of
-    the first step's gradients."""
+    """The oracle timed on a bounded sample of the step: the worker lines of Algorithm 2 (error
+    compensation + full-sort Top_K) on one worker row per thread of the first step's
+    gradients, then one whole server pass (aggregation of those rows' uplinks, full sort of
+    the d-length aggregate, residual, model update).  The worker time is scaled to N rows;
+    value = N d / (scaled worker time + server time)."""
     import numpy as np
     import oracle
+    import workloads as wl
+    oracle.build()
     threads = max(1, min(threads, cfg.N))
-    rows = min(2 * threads, cfg.N)
+    rows = min(threads, cfg.N)
     g = g_first[:rows].cpu().numpy()
     eps = np.zeros_like(g)
-    oracle.build()
     t0 = time.perf_counter()
-    oracle.worker_stage(g, eps, cfg.alpha, cfg.K_up, nthreads=threads)
-    dt = time.perf_counter() - t0
-    return {"value": rows * cfg.d / dt, "unit": "coords/s", "cores": threads, "kind": "oracle",
-            "sample": f"worker lines of Algorithm 2 (error compensation + full-sort Top_K) on "
-                      f"{rows} of {cfg.N} rows of {cfg.name} step 1, {threads} threads, "
-                      f"{dt:.1f} s; server stage not included"}
+    up_idx, up_val = oracle.worker_stage(g, eps, cfg.alpha, cfg.K_up, nthreads=threads)
+    t_worker = time.perf_counter() - t0
+    p = wl.p_weights(cfg)[:rows].copy()
+    delta = np.zeros(cfg.d, np.float32)
+    w = np.zeros(cfg.d, np.float32)
+    t0 = time.perf_counter()
+    oracle.aggregate(up_idx, up_val, p, delta)
+    dn_idx, dn_val = oracle.downlink(delta, cfg.K_dn)
+    oracle.update(dn_idx, dn_val, 1.0, w)
+    t_server = time.perf_counter() - t0
+    t_step = t_worker * cfg.N / rows + t_server
+    out = {"value": cfg.N * cfg.d / t_step, "unit": "coords/s", "cores": threads,
+           "kind": "oracle", "cpu_model": cpu_model(),
+           "worker_stage_s": t_worker, "server_stage_s": t_server,
+           "sample": f"{cfg.name} step 1: worker lines of Algorithm 2 on {rows} of {cfg.N} rows, "
+                     f"{threads} threads, {t_worker:.1f} s (scaled by {cfg.N}/{rows}); one server "
+                     f"pass (aggregation of those rows' uplinks, full sort of d = {cfg.d}, "
+                     f"update), 1 thread, {t_server:.1f} s"}
+    if cfg.N * cfg.d <= (1 << 23):           # small enough: the whole step on one thread too
+        g_all = g_first.cpu().numpy()
+        e1, d1, w1 = np.zeros_like(g_all), np.zeros(cfg.d, np.float32), np.zeros(cfg.d, np.float32)
+        t0 = time.perf_counter()
+        oracle.bidir_step(g_all, e1, d1, w1, wl.p_weights(cfg), cfg.K_up, cfg.K_dn, cfg.alpha, 1.0,
+                          nthreads=1)
+        t1 = time.perf_counter() - t0
+        out["one_thread"] = {"value": cfg.N * cfg.d / t1, "unit": "coords/s", "step_s": t1,
+                             "sample": f"the whole step of {cfg.name}, 1 thread"}
+    return out
+
+
+def source_digest() -> str:
+    """Digest of the kernel sources a recorded counter reading belongs to."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2209_15203_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(cfg_name):
+    """HBM bytes per launch of the dominant kernel from the committed counter record
+    (profiles/traffic.json: two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE, each scaled
+    by a copy kernel of known size).  Not measured by this run: returned with its source,
+    and as null when the kernel sources have changed since the record was taken."""
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        rec = json.load(open(tpath)).get(cfg_name)
+    except (OSError, ValueError):
+        rec = None
+    if not rec:
+        return None, "none recorded for this workload"
+    if rec.get("source_digest") != source_digest():
+        return None, "profiles/traffic.json is older than the kernel sources"
+    return rec.get("hbm_bytes_per_launch"), "profiles/traffic.json (rocprofv3 --pmc record)"
+
+
+def record_traffic(cfg_name, fetch_csv, write_csv) -> int:
+    """Turn the counter_collection.csv files of two rocprofv3 --pmc runs of
+    `bench.py --config <cfg> --calibrate-copy` (FETCH_SIZE, then WRITE_SIZE) into the
+    workload's entry of profiles/traffic.json."""
+    import csv
+
+    def read(path):
+        dom, cal = [], []
+        for r in csv.DictReader(open(path)):
+            name, v = r["Kernel_Name"], float(r["Counter_Value"])
+            if "k_stream_capture<true" in name:
+                dom.append(v)
+            elif "elementwise" in name and v > 400000.0:     # the 1 GiB calibration copy
+                cal.append(v)
+        if not dom or not cal:
+            raise SystemExit(f"{path}: dominant kernel or calibration copy not found")
+        return sum(dom) / len(dom), cal[-1], len(dom)
+
+    (f_kib, f_cal, n), (w_kib, w_cal, _) = read(fetch_csv), read(write_csv)
+    f_scale, w_scale = 1048576.0 / f_cal, 1048576.0 / w_cal
+    import workloads as wl
+    cfg = wl.CONFIGS[cfg_name]
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        tj = json.load(open(tpath))
+    except (OSError, ValueError):
+        tj = {}
+    fetch_b, write_b = f_kib * 1024.0 * f_scale, w_kib * 1024.0 * w_scale
+    tj[cfg_name] = {"kernel": "k_stream_capture<true>", "launches_averaged": n,
+                    "hbm_bytes_per_launch": fetch_b + write_b, "fetch_bytes": fetch_b,
+                    "write_bytes": write_b, "algorithmic_bytes": 12 * cfg.N * cfg.d,
+                    "fetch_scale": f_scale, "write_scale": w_scale,
+                    "source_digest": source_digest(),
+                    "note": "rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (KiB per dispatch), "
+                            "each scaled by the same counter's reading for a plain 1 GiB-in / "
+                            "1 GiB-out elementwise copy in the same run"}
+    json.dump(tj, open(tpath, "w"), indent=1)
+    print(json.dumps(tj[cfg_name], indent=1))
+    return 0
 
 
 def main() -> int:
@@ -80,6 +185,10 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="capture the step once per resident gradient batch into a HIP graph "
                          "and time the replays (cuts kernel-launch overhead on small shapes)")
+    ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: write the workload's entry of profiles/traffic.json from "
+                         "the counter_collection.csv files of two rocprofv3 --pmc runs "
+                         "(FETCH_SIZE, WRITE_SIZE) of this script with --calibrate-copy")
     ap.add_argument("--path", choices=["auto", "dense", "single"], default="auto",
                     help="select path: chosen by shape (default), dense multi-pass only, or "
                          "single-pass wherever the shape allows")
@@ -88,6 +197,9 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         return 2
+
+    if args.record_traffic:
+        return record_traffic(args.config, *args.record_traffic)
 
     import torch
 
@@ -121,6 +233,7 @@ def main() -> int:
     for b in range(n_buf):
         ring.append(src.step(b + 1))
     torch.cuda.synchronize()
+    checksums = [f"{wl.checksum(t):016x}" for t in ring]      # per (config, step) input batch
 
     side = torch.cuda.Stream(device=dev) if args.graph else None
     ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn, stream=side)
@@ -182,10 +295,17 @@ def main() -> int:
         n = src_p.numel() // 512 * 512
         out = {"probe": "plain streams with the dominant kernel's access shape",
                "floats": n, "peak_gbps": HBM_PEAK_GBS, "unit": "GB/s"}
+        from paper_2209_15203_amd import binding
         for kind, name, bytes_per in ((0, "read", 4), (1, "copy", 8), (2, "fma_stream", 12)):
-            ms = ctx.hbm_probe(kind, src_p, dst_p, repeats=max(1, args.steps))
-            out[name] = {"ms": ms, "gbps": bytes_per * n / ms / 1e6,
-                         "frac_of_peak": bytes_per * n / ms / 1e6 / HBM_PEAK_GBS}
+            # occupancy: every wave slot, or held to 12 / 20 / 24 waves per compute unit
+            # through unused LDS ("lds") or through the register allocation ("regs")
+            for waves, by_regs in ((0, False), (12, False), (12, True), (20, False), (20, True),
+                                   (24, False), (24, True)):
+                ms = binding.hbm_probe(kind, src_p, dst_p, waves, by_regs,
+                                       repeats=max(1, args.steps))
+                tag = name if waves == 0 else f"{name}_{waves}waves_{'regs' if by_regs else 'lds'}"
+                out[tag] = {"ms": ms, "gbps": bytes_per * n / ms / 1e6,
+                            "frac_of_peak": bytes_per * n / ms / 1e6 / HBM_PEAK_GBS}
         print(json.dumps(out))
         return 0
 
@@ -200,14 +320,23 @@ def main() -> int:
     for _ in range(args.warmup):
         step(it)
         it += 1
+    # per-step times: HIP events on the stream the library launches on (recorded inside the
+    # timed region: two event records per step)
+    ev_stream = side if side is not None else torch.cuda.current_stream()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    timed_batches = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(ev_stream)
+    for k in range(args.steps):
         step(it)
+        marks[k + 1].record(ev_stream)
+        timed_batches.append(it % n_buf)
         it += 1
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_step = [marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)]
     coords_per_s = N * d / (ms_per_step * 1e-3)
     b_alg = algorithmic_bytes(N, d, cfg.K_up, cfg.K_dn)
     if args.algo == "unidir":
@@ -229,14 +358,7 @@ def main() -> int:
     k_avg_ms = k_ms / max(k_n, 1)
     k_bytes = 12 * N * d
     achieved = k_bytes / (k_avg_ms * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            tj = json.load(open(tpath))
-            traffic = tj.get(cfg.name, {}).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    traffic, traffic_source = recorded_traffic(cfg.name)
 
     out = {
         "metric": {"bidir": "gradient coords/sec per bidirectional top-K step (N*d/s)",
@@ -266,7 +388,19 @@ def main() -> int:
                                                "writes eps)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "kernel_ms": k_avg_ms, "launches": k_n},
+        "step_ms": {"mean": sum(per_step) / len(per_step),
+                    "median": sorted(per_step)[len(per_step) // 2]
+                    if len(per_step) % 2 else
+                    0.5 * (sorted(per_step)[len(per_step) // 2 - 1] + sorted(per_step)[len(per_step) // 2]),
+                    "min": min(per_step), "max": max(per_step),
+                    "per_step": [round(v, 4) for v in per_step],
+                    "clock": "HIP events on the library's stream around each step"},
+        "input_checksums": {"seed": cfg.seed,
+                            "resident_batches": checksums,
+                            "batch_of_timed_step": timed_batches,
+                            "kind": "64-bit wrap-around sum of the fp32 words of g (N x d)"},
     }
     if args.algo == "bidir_diag":
         dg = diag.cpu().tolist()

@@ -231,5 +231,8 @@ class GradientSource:
 
 
 def checksum(t: torch.Tensor) -> int:
-    """64-bit wrap-around sum of the fp32 bit patterns (logged so runs can be compared)."""
+    """64-bit wrap-around sum of the fp32 bit patterns (logged so runs can be compared).
+    A matrix is summed row by row (the widened copy of a 28 GB batch would not fit)."""
+    if t.dim() >= 2:
+        return sum(checksum(r) for r in t) & _M64
     return int(t.contiguous().view(torch.int32).to(torch.int64).sum().item()) & _M64
