@@ -53,8 +53,8 @@ typedef struct bts_ctx bts_ctx;
  * K == d are legal.  hip_stream is a hipStream_t (host value, borrowed, may be null for
  * the default stream); every later call on the context queues onto it.  Scratch
  * (histograms, per-block counts, candidate lists, chunk directory, selection state) is sized and
- * cleared here once; the call synchronises the device before it returns (it is the only
- * call besides bts_destroy, bts_profile_read and bts_last_path that does).
+ * cleared here once; the call synchronises the device before it returns (of the calls
+ * declared here only bts_create, bts_enable_diagnostics and bts_destroy do).
  */
 int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_dn,
                void* hip_stream);
@@ -156,41 +156,6 @@ int bts_enable_diagnostics(bts_ctx* ctx);
 int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
                     const float* p, float alpha_in, float alpha_out, uint32_t* up_idx,
                     float* up_val, uint32_t* dn_idx, float* dn_val, double* diag);
-
-/*
- * Timing of the dominant kernel (the dense pass over g and eps in topk_compress).  While
- * enabled, the library brackets that kernel with HIP events on the context's stream.
- * bts_profile_read synchronises those events and returns the summed kernel time in
- * milliseconds and the number of launches since the last read (both host pointers).
- */
-int bts_profile_enable(bts_ctx* ctx, int on);
-int bts_profile_read(bts_ctx* ctx, double* ms_total, uint64_t* launches);
-
-/*
- * Measurement aid: a plain stream over n floats (device pointers, 16-byte aligned, n >= 512;
- * whole 512-float chunks only) with the dominant kernel's access shape and nothing else:
- * kind 0 reads src, kind 1 copies src to dst, kind 2 does dst = fma(0.5, src, dst) -- the
- * 2 reads : 1 write mix of the worker stage (Algorithm 2, worker line 1).  Queues one
- * untimed launch and `repeats` timed ones on the context's stream, waits for them, and
- * returns the mean time of one launch in milliseconds (host pointer).  kinds 1 and 2
- * overwrite dst.  Shows what fraction of the 8 TB/s peak such a stream reaches on the part.
- */
-int bts_hbm_probe(bts_ctx* ctx, int kind, const float* src, float* dst, uint64_t n,
-                  int repeats, double* ms_per_launch);
-
-/* Path taken by the last topk_compress / downlink_topk on this context, for tests and
- * reports: a host-synchronous read of per-row flags.  rows_fast = rows finished by the
- * single-pass path, rows_dense = all others (dense multi-pass path, or the one-workgroup
- * path of short rows); rows_fast + rows_dense == rows.  which: 0 = uplink, 1 = downlink. */
-int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_dense);
-
-/* Testing aid: which select path later calls on this context take.  0 (default): chosen
- * by shape (one workgroup per row up to d = 8192, else dense multi-pass, else single-pass
- * from about 1.1e7 coordinates per call, 2.5e7 for a single row); 1: the dense multi-pass
- * path only (the path that also serves as the fallback); 2: the single-pass path wherever
- * the shape allows it (d >= 65536 and K <= d/64), whatever its size.  Results are identical
- * in every mode. */
-int bts_set_path(bts_ctx* ctx, int mode);
 
 #ifdef __cplusplus
 }

@@ -12,10 +12,16 @@ _LIB_PATH = os.path.join(_HERE, "libbts.so")
 
 EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
            "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
-           "unidir_step", "bts_enable_diagnostics", "bidir_step_diag", "bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path",
-           "bts_hbm_probe"]
+           "unidir_step", "bts_enable_diagnostics", "bidir_step_diag"]
+# testing and measurement aids of the same library (include/bts_testing.h)
+TESTING_EXPORTS = ["bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path",
+                   "bts_testing_mark_dirty"]
+# the measurement instrument, a library of its own (include/bts_probe.h)
+PROBE_EXPORTS = ["bts_hbm_probe"]
+_PROBE_PATH = os.path.join(_HERE, "libbts_probe.so")
 
 _lib = None
+_probe = None
 
 
 class BtsError(RuntimeError):
@@ -53,21 +59,56 @@ def load_library():
     lib.bts_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64)]
     lib.bts_last_path.argtypes = [vp, C.c_int, C.POINTER(u32), C.POINTER(u32)]
     lib.bts_set_path.argtypes = [vp, C.c_int]
-    for name in EXPORTS:
+    lib.bts_testing_mark_dirty.argtypes = [vp]
+    for name in EXPORTS + TESTING_EXPORTS:
         if name != "bts_destroy":
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
 
 
+def load_probe_library():
+    """Load libbts_probe.so (plain HBM streams; a measurement instrument, not the product)."""
+    global _probe
+    if _probe is None:
+        if not os.path.exists(_PROBE_PATH):
+            raise BtsError(f"{_PROBE_PATH} is missing: python -m paper_2209_15203_amd.build")
+        lib = C.CDLL(_PROBE_PATH)
+        lib.bts_hbm_probe.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_uint64,
+                                      C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
+        lib.bts_hbm_probe.restype = C.c_int
+        _probe = lib
+    return _probe
+
+
+def hbm_probe(kind: int, src: torch.Tensor, dst: torch.Tensor, waves_per_cu: int = 0,
+              by_registers: bool = False, repeats: int = 5) -> float:
+    """Mean milliseconds of one plain stream over src/dst (0 read, 1 copy, 2 fma-stream) on
+    the current torch stream."""
+    ms = C.c_double(0.0)
+    n = min(src.numel(), dst.numel())
+    rc = load_probe_library().bts_hbm_probe(
+        C.c_void_p(torch.cuda.current_stream().cuda_stream), int(kind),
+        _ptr(src, torch.float32, "src"), _ptr(dst, torch.float32, "dst"), C.c_uint64(n),
+        int(waves_per_cu), int(by_registers), int(repeats), C.byref(ms))
+    if rc != 0:
+        raise BtsError(f"bts_hbm_probe failed: {rc}")
+    return ms.value
+
+
 _CODES = {-1: "BTS_EINVAL", -2: "BTS_ENOMEM", -3: "BTS_EHIP"}
 
 
-def _ptr(t: Optional[torch.Tensor], dtype, name: str):
+def _ptr(t: Optional[torch.Tensor], dtype, name: str, numel: Optional[int] = None):
+    """Device pointer of a tensor argument.  numel: the elements the library will read or
+    write there; a smaller tensor is refused here, on the host, because the kernels would
+    run past its end."""
     if t is None:
         return None
     if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise TypeError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+    if numel is not None and t.numel() < numel:
+        raise TypeError(f"{name} has {t.numel()} elements, the call needs {numel}")
     return C.c_void_p(t.data_ptr())
 
 
@@ -116,21 +157,16 @@ class BtsContext:
         self.check(self._lib.bts_profile_read(self._h, C.byref(ms), C.byref(n)), "bts_profile_read")
         return ms.value, n.value
 
-    def hbm_probe(self, kind: int, src: torch.Tensor, dst: torch.Tensor, repeats: int = 5) -> float:
-        """Mean milliseconds of one plain stream over src/dst (0 read, 1 copy, 2 fma-stream)."""
-        ms = C.c_double(0.0)
-        n = min(src.numel(), dst.numel())
-        self.check(self._lib.bts_hbm_probe(self._h, int(kind), _ptr(src, torch.float32, "src"),
-                                           _ptr(dst, torch.float32, "dst"), C.c_uint64(n),
-                                           int(repeats), C.byref(ms)), "bts_hbm_probe")
-        return ms.value
-
     def enable_diagnostics(self) -> None:
         self.check(self._lib.bts_enable_diagnostics(self._h), "bts_enable_diagnostics")
 
     def set_path(self, mode: int) -> None:
         """0 = by shape, 1 = dense path only, 2 = single-pass path wherever possible."""
         self.check(self._lib.bts_set_path(self._h, int(mode)), "bts_set_path")
+
+    def testing_mark_dirty(self) -> None:
+        """Testing aid: the next calls behave as after a call that failed half way."""
+        self.check(self._lib.bts_testing_mark_dirty(self._h), "bts_testing_mark_dirty")
 
     def last_path(self, which: int) -> Tuple[int, int]:
         a, b = C.c_uint32(0), C.c_uint32(0)
@@ -142,54 +178,65 @@ F32, U32 = torch.float32, torch.int32   # uint32 words travel in int32 tensors
 
 
 def topk_compress(ctx: BtsContext, g, eps, alpha_in: float, up_idx, up_val) -> None:
-    ctx.check(ctx._lib.topk_compress(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"), alpha_in,
-                                     _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val")),
-              "topk_compress")
+    nd, nk = ctx.N * ctx.d, ctx.N * ctx.K_up
+    ctx.check(ctx._lib.topk_compress(ctx._h, _ptr(g, F32, "g", nd), _ptr(eps, F32, "eps", nd),
+                                     alpha_in, _ptr(up_idx, U32, "up_idx", nk),
+                                     _ptr(up_val, F32, "up_val", nk)), "topk_compress")
 
 
 def sparse_aggregate(ctx: BtsContext, up_idx, up_val, p, delta, union_nnz=None) -> None:
-    ctx.check(ctx._lib.sparse_aggregate(ctx._h, _ptr(up_idx, U32, "up_idx"),
-                                        _ptr(up_val, F32, "up_val"), _ptr(p, F32, "p"),
-                                        _ptr(delta, F32, "delta"),
-                                        _ptr(union_nnz, U32, "union_nnz")), "sparse_aggregate")
+    nk = ctx.N * ctx.K_up
+    ctx.check(ctx._lib.sparse_aggregate(ctx._h, _ptr(up_idx, U32, "up_idx", nk),
+                                        _ptr(up_val, F32, "up_val", nk),
+                                        _ptr(p, F32, "p", ctx.N), _ptr(delta, F32, "delta", ctx.d),
+                                        _ptr(union_nnz, U32, "union_nnz", 1)), "sparse_aggregate")
 
 
 def downlink_topk(ctx: BtsContext, delta, dn_idx, dn_val) -> None:
-    ctx.check(ctx._lib.downlink_topk(ctx._h, _ptr(delta, F32, "delta"),
-                                     _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val")),
-              "downlink_topk")
+    ctx.check(ctx._lib.downlink_topk(ctx._h, _ptr(delta, F32, "delta", ctx.d),
+                                     _ptr(dn_idx, U32, "dn_idx", ctx.K_dn),
+                                     _ptr(dn_val, F32, "dn_val", ctx.K_dn)), "downlink_topk")
 
 
 def sparse_sgd_update(ctx: BtsContext, idx, val, K: int, alpha_out: float, w) -> None:
-    ctx.check(ctx._lib.sparse_sgd_update(ctx._h, _ptr(idx, U32, "idx"), _ptr(val, F32, "val"), K,
-                                         alpha_out, _ptr(w, F32, "w")), "sparse_sgd_update")
+    ctx.check(ctx._lib.sparse_sgd_update(ctx._h, _ptr(idx, U32, "idx", K), _ptr(val, F32, "val", K),
+                                         K, alpha_out, _ptr(w, F32, "w", ctx.d)),
+              "sparse_sgd_update")
+
+
+def _step_ptrs(ctx: BtsContext, g, eps, w, p, up_idx, up_val):
+    nd, nk = ctx.N * ctx.d, ctx.N * ctx.K_up
+    return (_ptr(g, F32, "g", nd), _ptr(eps, F32, "eps", nd), _ptr(w, F32, "w", ctx.d),
+            _ptr(p, F32, "p", ctx.N), _ptr(up_idx, U32, "up_idx", nk),
+            _ptr(up_val, F32, "up_val", nk))
 
 
 def bidir_step(ctx: BtsContext, g, eps, delta, w, p, alpha_in: float, alpha_out: float,
                up_idx, up_val, dn_idx, dn_val, union_nnz=None) -> None:
-    ctx.check(ctx._lib.bidir_step(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"),
-                                  _ptr(delta, F32, "delta"), _ptr(w, F32, "w"), _ptr(p, F32, "p"),
-                                  alpha_in, alpha_out, _ptr(up_idx, U32, "up_idx"),
-                                  _ptr(up_val, F32, "up_val"), _ptr(dn_idx, U32, "dn_idx"),
-                                  _ptr(dn_val, F32, "dn_val"),
-                                  _ptr(union_nnz, U32, "union_nnz")), "bidir_step")
+    pg, pe, pw, pp, pui, puv = _step_ptrs(ctx, g, eps, w, p, up_idx, up_val)
+    ctx.check(ctx._lib.bidir_step(ctx._h, pg, pe, _ptr(delta, F32, "delta", ctx.d), pw, pp,
+                                  alpha_in, alpha_out, pui, puv,
+                                  _ptr(dn_idx, U32, "dn_idx", ctx.K_dn),
+                                  _ptr(dn_val, F32, "dn_val", ctx.K_dn),
+                                  _ptr(union_nnz, U32, "union_nnz", 1)), "bidir_step")
 
 
 def unidir_step(ctx: BtsContext, g, eps, w, p, alpha_in: float, alpha_out: float, up_idx, up_val,
                 dn_idx=None, dn_val=None, dn_count=None) -> None:
-    ctx.check(ctx._lib.unidir_step(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"),
-                                   _ptr(w, F32, "w"), _ptr(p, F32, "p"), alpha_in, alpha_out,
-                                   _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val"),
-                                   _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val"),
-                                   _ptr(dn_count, U32, "dn_count")), "unidir_step")
+    pg, pe, pw, pp, pui, puv = _step_ptrs(ctx, g, eps, w, p, up_idx, up_val)
+    nk = ctx.N * ctx.K_up
+    ctx.check(ctx._lib.unidir_step(ctx._h, pg, pe, pw, pp, alpha_in, alpha_out, pui, puv,
+                                   _ptr(dn_idx, U32, "dn_idx", nk), _ptr(dn_val, F32, "dn_val", nk),
+                                   _ptr(dn_count, U32, "dn_count", 1)), "unidir_step")
 
 
 def bidir_step_diag(ctx: BtsContext, g, eps, delta, w, p, alpha_in: float, alpha_out: float,
                     up_idx, up_val, dn_idx, dn_val, diag) -> None:
     """diag: float64 tensor of 8 + N elements on the GPU."""
-    ctx.check(ctx._lib.bidir_step_diag(ctx._h, _ptr(g, F32, "g"), _ptr(eps, F32, "eps"),
-                                       _ptr(delta, F32, "delta"), _ptr(w, F32, "w"),
-                                       _ptr(p, F32, "p"), alpha_in, alpha_out,
-                                       _ptr(up_idx, U32, "up_idx"), _ptr(up_val, F32, "up_val"),
-                                       _ptr(dn_idx, U32, "dn_idx"), _ptr(dn_val, F32, "dn_val"),
-                                       _ptr(diag, torch.float64, "diag")), "bidir_step_diag")
+    pg, pe, pw, pp, pui, puv = _step_ptrs(ctx, g, eps, w, p, up_idx, up_val)
+    ctx.check(ctx._lib.bidir_step_diag(ctx._h, pg, pe, _ptr(delta, F32, "delta", ctx.d), pw, pp,
+                                       alpha_in, alpha_out, pui, puv,
+                                       _ptr(dn_idx, U32, "dn_idx", ctx.K_dn),
+                                       _ptr(dn_val, F32, "dn_val", ctx.K_dn),
+                                       _ptr(diag, torch.float64, "diag", 8 + ctx.N)),
+              "bidir_step_diag")

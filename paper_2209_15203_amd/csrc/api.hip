@@ -2,6 +2,7 @@
 // in which the kernels of one step of Algorithm 2 are queued.
 
 #include "../../include/bts.h"
+#include "../../include/bts_testing.h"
 
 #include <new>
 #include <vector>
@@ -22,6 +23,9 @@ struct bts_ctx {
   bool fast_up_dirty, fast_dn_dirty;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
+  FastPlan plan_diag_u;         // diagnostics: one row of length d with K_up (the select of
+  FastScratch fast_diag_u;      //   sum_q p_q a^q); the one with K_dn reuses plan_dn / fast_dn
+  bool fast_diag_u_dirty;
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
   uint32_t* agg_offsets;        // their exclusive scan (unidirectional message placement)
   uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
@@ -38,6 +42,8 @@ struct bts_ctx {
 };
 
 namespace {
+
+constexpr size_t kMaxProfileEvents = 4096;   // launches recorded between two bts_profile_read
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -112,6 +118,7 @@ void release(bts_ctx* ctx) {
 void profile_events(bts_ctx* ctx, hipEvent_t* e0, hipEvent_t* e1) {
   *e0 = *e1 = nullptr;
   if (!ctx->profile) return;
+  if (ctx->ev_used == kMaxProfileEvents) return;     // unread for too long: stop recording
   if (ctx->ev_used == ctx->ev_pool.size()) {
     hipEvent_t a, b;
     if (hipEventCreate(&a) != hipSuccess) return;
@@ -134,8 +141,10 @@ bool use_fast(const bts_ctx* ctx, const FastPlan& pl) {
 // uplink = true: the N worker rows with the error compensation fused in; false: the one
 // server row.  The single-pass path runs first where the plan enables it; rows it flags
 // (and every row where it is not enabled) go through the dense path.
+// energy (diagnostics, uplink only): the single-pass path also leaves the partial sums of the
+// rows' residual energies in its scratch; *energy is cleared if another path ran.
 int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha, uint32_t* idx,
-               float* val) {
+               float* val, bool* energy = nullptr) {
   const uint32_t rows = uplink ? (uint32_t)ctx->N : 1u;
   const uint32_t K = uplink ? ctx->K_up : ctx->K_dn;
   const FastPlan& pl = uplink ? ctx->plan_up : ctx->plan_dn;
@@ -143,6 +152,8 @@ int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha,
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (uplink) profile_events(ctx, &e0, &e1);
   hipError_t e;
+  const bool want_energy = energy != nullptr && *energy && fs.energy != nullptr;
+  if (energy != nullptr) *energy = false;
   if (K == 0) {
     if (g == nullptr) return BTS_OK;
     e = axpy_only(ctx->stream, g, x, rows, ctx->d, alpha, e0, e1);
@@ -150,12 +161,25 @@ int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha,
     e = row_select(ctx->stream, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
   } else if (use_fast(ctx, pl)) {
     e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1,
-                    ctx->dense);
+                    ctx->dense, want_energy);
+    if (energy != nullptr) *energy = want_energy;
   } else {
     e = dense_select(ctx->stream, ctx->dense, g, x, rows, ctx->d, K, alpha, idx, val, nullptr,
                      false, e0, e1);
   }
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
+}
+
+// Every argument check of a whole step (bidir_step and bidir_step_diag), made before
+// anything is queued.
+bool step_args_ok(const bts_ctx* ctx, const float* g, const float* eps, const float* delta,
+                  const float* w, const float* p, const uint32_t* up_idx, const float* up_val,
+                  const uint32_t* dn_idx, const float* dn_val) {
+  if (!ctx || !g || !eps || !delta || !w || !p) return false;
+  if (!aligned16(g) || !aligned16(eps) || !aligned16(delta)) return false;
+  if (ctx->K_up > 0 && (!up_idx || !up_val)) return false;
+  if (ctx->K_dn > 0 && (!dn_idx || !dn_val)) return false;
+  return true;
 }
 
 }  // namespace
@@ -181,9 +205,11 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->path_mode = 0;
   ctx->dense = DenseScratch{};
   ctx->dense_dirty = false;
-  ctx->fast_up_dirty = ctx->fast_dn_dirty = false;
+  ctx->fast_up_dirty = ctx->fast_dn_dirty = ctx->fast_diag_u_dirty = false;
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
+  ctx->fast_diag_u = FastScratch{};
+  ctx->plan_diag_u = FastPlan{};
   ctx->agg_ranges = nullptr;
   ctx->diag = DiagScratch{};
   ctx->diag_ready = false;
@@ -278,10 +304,7 @@ int sparse_sgd_update(bts_ctx* ctx, const uint32_t* idx, const float* val, uint3
 int bidir_step(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w, const float* p,
                float alpha_in, float alpha_out, uint32_t* up_idx, float* up_val,
                uint32_t* dn_idx, float* dn_val, uint32_t* union_nnz) {
-  if (!ctx || !g || !eps || !delta || !w || !p) return BTS_EINVAL;
-  if (!aligned16(g) || !aligned16(eps) || !aligned16(delta)) return BTS_EINVAL;
-  if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
-  if (ctx->K_dn > 0 && (!dn_idx || !dn_val)) return BTS_EINVAL;
+  if (!step_args_ok(ctx, g, eps, delta, w, p, up_idx, up_val, dn_idx, dn_val)) return BTS_EINVAL;
   int rc = topk_compress(ctx, g, eps, alpha_in, up_idx, up_val);
   if (rc != BTS_OK) return rc;
   rc = sparse_aggregate(ctx, up_idx, up_val, p, delta, union_nnz);
@@ -319,6 +342,17 @@ int bts_enable_diagnostics(bts_ctx* ctx) {
             dev_alloc(ctx, &ds.c_idx, (size_t)ctx->K_up) &&
             dev_alloc(ctx, &ds.c_val, (size_t)ctx->K_up) && dev_alloc(ctx, &ds.m_idx, nk) &&
             dev_alloc(ctx, &ds.m_val, nk) && dev_alloc(ctx, &ds.m_cnt, 1);
+  if (ok) {                            // the one-row select with K_up (falls back to dense)
+    ctx->plan_diag_u = fast_plan(1, ctx->d, ctx->K_up);
+    ctx->fast_diag_u.dirty = &ctx->fast_diag_u_dirty;
+    if (!alloc_fast(ctx, ctx->plan_diag_u, 1, &ctx->fast_diag_u)) {
+      (void)hipGetLastError();
+      ctx->plan_diag_u.enabled = false;
+    }
+  }
+  if (ok && ctx->plan_up.enabled)      // partial sums of the rows' residual energies
+    ok = dev_alloc(ctx, &ctx->fast_up.energy, (size_t)ctx->N * ctx->plan_up.nwc_pad) &&
+         dev_alloc(ctx, &ctx->fast_up.tile_energy, (size_t)ctx->N * ctx->plan_up.ntiles);
   if (!ok) {
     (void)hipGetLastError();
     return BTS_ENOMEM;
@@ -331,17 +365,34 @@ int bts_enable_diagnostics(bts_ctx* ctx) {
 int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
                     const float* p, float alpha_in, float alpha_out, uint32_t* up_idx,
                     float* up_val, uint32_t* dn_idx, float* dn_val, double* diag) {
-  if (!ctx || !diag || !g || !eps || !delta || !p) return BTS_EINVAL;
+  if (!diag || !step_args_ok(ctx, g, eps, delta, w, p, up_idx, up_val, dn_idx, dn_val))
+    return BTS_EINVAL;
   if (!ctx->diag_ready || ctx->K_up == 0 || ctx->K_dn == 0) return BTS_EINVAL;
   hipError_t e = diag_before_step(ctx->stream, ctx->diag, g, eps, delta, p, (uint32_t)ctx->N,
                                   ctx->d, alpha_in);
   if (e != hipSuccess) return fail_hip(ctx, e);
-  int rc = bidir_step(ctx, g, eps, delta, w, p, alpha_in, alpha_out, up_idx, up_val, dn_idx,
-                      dn_val, nullptr);
+  // the step itself, with the worker compression also leaving the rows' residual energies
+  bool energy = true;
+  int rc = run_select(ctx, true, g, eps, alpha_in, up_idx, up_val, &energy);
   if (rc != BTS_OK) return rc;
+  rc = sparse_aggregate(ctx, up_idx, up_val, p, delta, nullptr);
+  if (rc != BTS_OK) return rc;
+  rc = downlink_topk(ctx, delta, dn_idx, dn_val);
+  if (rc != BTS_OK) return rc;
+  rc = sparse_sgd_update(ctx, dn_idx, dn_val, ctx->K_dn, alpha_out, w);
+  if (rc != BTS_OK) return rc;
+  RowEnergy re{};
+  if (energy) {
+    re.chunks = ctx->fast_up.energy;
+    re.tiles = ctx->fast_up.tile_energy;
+    re.nwc_pad = ctx->plan_up.nwc_pad;
+    re.ntiles = ctx->plan_up.ntiles;
+    re.need = ctx->fast_up.need;
+  }
   e = diag_after_step(ctx->stream, ctx->diag, ctx->dense, eps, delta, p, (uint32_t)ctx->N, ctx->d,
                       ctx->K_up, ctx->K_dn, alpha_in, up_idx, up_val, dn_idx, dn_val,
-                      agg_scratch(ctx), diag);
+                      agg_scratch(ctx), re, OneRowSelect{&ctx->plan_dn, &ctx->fast_dn},
+                      OneRowSelect{&ctx->plan_diag_u, &ctx->fast_diag_u}, diag);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -389,13 +440,12 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
   return BTS_OK;
 }
 
-int bts_hbm_probe(bts_ctx* ctx, int kind, const float* src, float* dst, uint64_t n,
-                  int repeats, double* ms_per_launch) {
-  if (!ctx || !src || !dst || !ms_per_launch || kind < 0 || kind > 2 || repeats < 1 || n < 512)
-    return BTS_EINVAL;
-  if (!aligned16(src) || !aligned16(dst)) return BTS_EINVAL;
-  const hipError_t e = hbm_probe(ctx->stream, kind, src, dst, n, 0.5f, repeats, ms_per_launch);
-  return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
+int bts_testing_mark_dirty(bts_ctx* ctx) {
+  if (!ctx) return BTS_EINVAL;
+  ctx->dense_dirty = true;
+  ctx->fast_up_dirty = ctx->fast_dn_dirty = ctx->fast_diag_u_dirty = true;
+  ctx->agg_tables_bad = true;
+  return BTS_OK;
 }
 
 int bts_set_path(bts_ctx* ctx, int mode) {

@@ -9,14 +9,8 @@ namespace bts {
 constexpr int kWave = 64;                 // CDNA wavefront
 constexpr int kBlock = 256;               // threads per workgroup in the dense passes
 constexpr int kWavesPerBlock = kBlock / kWave;
-#ifndef BTS_UNROLL
-#define BTS_UNROLL 2
-#endif
-#ifndef BTS_STREAM_BLOCK
-#define BTS_STREAM_BLOCK 128
-#endif
-constexpr int kUnroll = BTS_UNROLL;       // float4 loads in flight per lane and array
-constexpr int kStreamBlock = BTS_STREAM_BLOCK;   // threads per workgroup of the dominant kernel
+constexpr int kUnroll = 2;                // float4 loads in flight per lane and array
+constexpr int kStreamBlock = 128;         // threads per workgroup of the dominant kernel
 constexpr int kStreamWaves = kStreamBlock / kWave;
 // Dynamic LDS requested (and never touched) by a plain stream of 2 reads : 1 write over
 // N x d, only to hold it to 6 workgroups = 12 waves per compute unit: with every wave slot
@@ -110,6 +104,10 @@ struct FastScratch {
   void* tile_cnt;          // rows x ntiles 64-bit words (rewritten by every call)
   bool* dirty;             // host flag: a call failed half way, clear directory and sample first
   uint32_t rows;           // rows the scratch was sized for
+  // diagnostics only (null otherwise): fp64 sums of squares of what stays behind in the row,
+  // per wave chunk (coordinates not captured) and per directory tile (captured, not kept)
+  double* energy;          // rows x nwc_pad; slots of chunks outside the row stay zero
+  double* tile_energy;     // rows x ntiles
 };
 
 FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K);
@@ -124,7 +122,7 @@ size_t fast_hist_words();
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
-                       const DenseScratch& dense);
+                       const DenseScratch& dense, bool energy);
 
 // ---- server side ------------------------------------------------------------------------
 uint32_t aggregate_ranges(uint64_t d);
@@ -161,21 +159,31 @@ struct DiagScratch {
   uint32_t* m_cnt;
 };
 size_t diag_part_doubles(uint32_t N);
+// Residual energies of the worker rows as the single-pass select left them (null chunks:
+// not available, every row is summed from eps).
+struct RowEnergy {
+  const double* chunks;    // rows x nwc_pad
+  const double* tiles;     // rows x ntiles
+  uint32_t nwc_pad, ntiles;
+  const uint32_t* need;    // rows the select handed to the dense path: summed from eps
+};
 hipError_t diag_before_step(hipStream_t s, const DiagScratch& ds, const float* g,
                             const float* eps, const float* delta, const float* p, uint32_t N,
                             uint64_t d, float alpha);
+// A single-pass select for one row of length d (null plan: the dense path does it).
+struct OneRowSelect {
+  const FastPlan* plan;
+  const FastScratch* scratch;
+};
 hipError_t diag_after_step(hipStream_t s, const DiagScratch& ds, const DenseScratch& dense,
                            const float* eps, const float* delta, const float* p, uint32_t N,
                            uint64_t d, uint32_t K_up, uint32_t K_dn, float alpha,
                            const uint32_t* up_idx, const float* up_val, const uint32_t* dn_idx,
-                           const float* dn_val, const AggScratch& agg, double* diag);
+                           const float* dn_val, const AggScratch& agg, const RowEnergy& energy,
+                           const OneRowSelect& sel_v, const OneRowSelect& sel_u, double* diag);
 
 hipError_t sgd_update(hipStream_t s, const uint32_t* idx, const float* val, uint32_t K,
                       float alpha_out, float* w, uint64_t d);
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v);
-
-// Plain streams with the dominant kernel's access shape (kind 0 read, 1 copy, 2 fma-stream).
-hipError_t hbm_probe(hipStream_t s, int kind, const float* src, float* dst, uint64_t n,
-                     float alpha, int repeats, double* ms_per_launch);
 
 }  // namespace bts

@@ -205,11 +205,22 @@ __device__ __forceinline__ void append_run(uint32_t flags, const float (&v)[kUnr
   }
 }
 
-template <bool FMA>
+// ENERGY (diagnostics only): the wave also sums, in fp64, the squares of its chunk's
+// coordinates that are NOT captured and stores the sum at energy[row * nwc_pad + wc]; with
+// the squares of the captured-but-not-kept entries (added up by the emission) that is the
+// row's residual energy |a - Top_K(a)|^2 without another pass over the row.
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+template <bool FMA, bool ENERGY>
 __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
     const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
     const uint32_t* __restrict__ lower_key, uint32_t* __restrict__ cand_cnt,
-    uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir, uint32_t nwc_pad) {
+    uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir, uint32_t nwc_pad,
+    double* __restrict__ energy) {
   const uint32_t row = blockIdx.y;
   const uint32_t wc = blockIdx.x * kStreamWaves + threadIdx.x / kWave;
   const ChunkGeom c = wave_chunk(d, row, wc);
@@ -222,8 +233,10 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
   const uint64_t e0 = c.base + (uint64_t)lane_id() * 4;
   const uint32_t i0 = (uint32_t)(e0 - c.lo);
   uint32_t flags = 0;
+  uint32_t in_row = 0;                       // ENERGY: which of the lane's elements are the row's
   float v[kUnroll][4];
   if (c.full) {
+    in_row = (1u << (4 * kUnroll)) - 1u;
     f4 xv[kUnroll];
     f4 gv[kUnroll];
 #pragma unroll
@@ -257,8 +270,19 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
         v[u][j] = vv[j];
         flags |= (((mask >> j) & 1u) && key_of(vv[j]) >= L ? 1u : 0u) << (4 * u + j);
       }
+      in_row |= mask << (4 * u);
       ++u;
     });
+  }
+  if (ENERGY) {
+    double e = 0.0;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if ((in_row & ~flags) & (1u << (4 * u + j))) e += (double)v[u][j] * (double)v[u][j];
+    e = wave_sum_f64(e);
+    if (lane_id() == 0) energy[(uint64_t)row * nwc_pad + wc] = e;
   }
   append_run(flags, v, i0, counter, list, cap, dir_entry);
 }
@@ -519,13 +543,16 @@ __device__ __forceinline__ void dir_scan_body(uint32_t row,
   }
 }
 
+// tile_energy (diagnostics only, else null): per tile, the fp64 sum of the squares of the
+// tile's entries that are not kept.
 template <int TPW>
 __device__ __forceinline__ void dir_emit_body(
     uint32_t bx, uint32_t row, uint2* __restrict__ dir, uint32_t nwc_pad,
     const uint2* __restrict__ cand, uint32_t cap, const FastSel* __restrict__ sel,
     const uint32_t* __restrict__ need, const unsigned long long* __restrict__ tile_cnt,
     uint32_t ntiles, float* __restrict__ x, uint64_t d, uint32_t K,
-    uint32_t* __restrict__ out_idx, float* __restrict__ out_val) {
+    uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
+    double* __restrict__ tile_energy) {
   __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
   const uint32_t w = threadIdx.x / kWave;
   const uint32_t quarter = (ntiles + TPW - 1) / TPW;
@@ -550,7 +577,12 @@ __device__ __forceinline__ void dir_emit_body(
   for (int u = 0; u < TPW; ++u) {
     const uint32_t tile = v + u * quarter;
     if (tile >= ntiles) break;
-    if (__ballot(ent[u].y != 0) == 0) continue;
+    if (__ballot(ent[u].y != 0) == 0) {
+      if (tile_energy != nullptr && lane_id() == 0)
+        tile_energy[(uint64_t)row * ntiles + tile] = 0.0;
+      continue;
+    }
+    double left = 0.0;                           // squares of the entries that stay behind
     const TileView t = publish_tile(ent[u], s_off[w], s_start[w]);
     const unsigned long long before = tile_cnt[(uint64_t)row * ntiles + tile];
     uint32_t run_gt = (uint32_t)before, run_eq = (uint32_t)(before >> 32);
@@ -578,10 +610,17 @@ __device__ __forceinline__ void dir_emit_body(
             ov[pos] = __uint_as_float(en[k].y);
             xr[idx] = 0.0f;
           }
+        } else if (e < t.total) {
+          const double val = (double)__uint_as_float(en[k].y);
+          left += val * val;
         }
         run_gt += __popcll(m_gt);
         run_eq += __popcll(m_eq);
       }
+    }
+    if (tile_energy != nullptr) {
+      left = wave_sum_f64(left);
+      if (lane_id() == 0) tile_energy[(uint64_t)row * ntiles + tile] = left;
     }
   }
 }
@@ -648,10 +687,10 @@ template <int TPW>
 __global__ __launch_bounds__(kBlock) void k_diremit_count(
     uint32_t own, uint32_t own_gx, uint2* dir, uint32_t nwc_pad, const uint2* cand, uint32_t cap,
     const FastSel* sel, const uint32_t* need, const unsigned long long* tile_cnt,
-    uint32_t ntiles, uint32_t* out_idx, float* out_val, DensePart dp) {
+    uint32_t ntiles, uint32_t* out_idx, float* out_val, double* tile_energy, DensePart dp) {
   if (blockIdx.x < own)
     dir_emit_body<TPW>(blockIdx.x % own_gx, blockIdx.x / own_gx, dir, nwc_pad, cand, cap, sel,
-                       need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val);
+                       need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val, tile_energy);
   else
     count_body(dense_vgrid(blockIdx.x - own, dp), dp.x, dp.d, dp.K, dp.hist, dp.state,
                dp.cnt_gt, dp.cnt_eq, dp.nwc, need, dp.streaming);
@@ -718,8 +757,11 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
-                       const DenseScratch& dense) {
+                       const DenseScratch& dense, bool energy) {
   const dim3 block(kBlock);
+  if (energy && (g == nullptr || sc.energy == nullptr || sc.tile_energy == nullptr))
+    return hipErrorInvalidValue;
+  double* tile_energy = energy ? sc.tile_energy : nullptr;
   const uint32_t nwc = (uint32_t)((d + kWaveChunk - 1) / kWaveChunk) + 1;
   const dim3 dense_grid((nwc + kStreamWaves - 1) / kStreamWaves, rows);
   unsigned long long* tile_cnt = reinterpret_cast<unsigned long long*>(sc.tile_cnt);
@@ -747,12 +789,17 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   // 2. the dense pass (a wave of the grid may lie past the row's last chunk, never past
   // the padded directory)
   if (ev0) (void)hipEventRecord(ev0, s);
-  if (g != nullptr)
-    k_stream_capture<true><<<dense_grid, dim3(kStreamBlock), pl.stream_lds, s>>>(
-        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad);
+  if (g != nullptr && energy)
+    k_stream_capture<true, true><<<dense_grid, dim3(kStreamBlock), pl.stream_lds, s>>>(
+        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad,
+        sc.energy);
+  else if (g != nullptr)
+    k_stream_capture<true, false><<<dense_grid, dim3(kStreamBlock), pl.stream_lds, s>>>(
+        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad, nullptr);
   else
-    k_stream_capture<false><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
-        nullptr, x, d, 0.0f, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad);
+    k_stream_capture<false, false><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
+        nullptr, x, d, 0.0f, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad,
+        nullptr);
   BTS_LAUNCH_CHECK();
   if (ev1) (void)hipEventRecord(ev1, s);
   // 3 + 4. verify and select: a few fat blocks per row, each taking whole lists (about 32768
@@ -807,11 +854,13 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   if (sparse_tiles)
     k_diremit_count<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
                                                     pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                                    tile_cnt, pl.ntiles, out_idx, out_val, dp);
+                                                    tile_cnt, pl.ntiles, out_idx, out_val,
+                                                    tile_energy, dp);
   else
     k_diremit_count<1><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
                                                     pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                                    tile_cnt, pl.ntiles, out_idx, out_val, dp);
+                                                    tile_cnt, pl.ntiles, out_idx, out_val,
+                                                    tile_energy, dp);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   // the rest of the redo: scan of the per-chunk counts, emission of the flagged rows

@@ -1,8 +1,13 @@
-// Measurement aid: what this part's HBM sustains for the access mixes of the library, with
-// the dominant kernel's access shape (one wave per 512 coordinates, two 16-byte non-temporal
-// accesses per lane and array in flight, 128-thread workgroups) and nothing else in the
-// kernel.  The dominant kernel of the worker stage is priced against the 8 TB/s peak; these
-// probes show how much of that peak a plain stream of the same read : write mix reaches.
+// libbts_probe: a measurement instrument, not part of libbts.  What this part's HBM sustains
+// for the access mixes of the library, with the dominant kernel's access shape (one wave per
+// 512 coordinates, two 16-byte non-temporal accesses per lane and array in flight,
+// 128-thread workgroups) and nothing else in the kernel.  The dominant kernel of the worker
+// stage is priced against the 8 TB/s peak; these probes show how much of that peak a plain
+// stream of the same read : write mix reaches, at full occupancy and held to fewer waves
+// per compute unit in the two ways a launch can be held (LDS it requests and never touches;
+// a register budget set by the waves-per-SIMD attribute).
+
+#include "../../include/bts_probe.h"
 
 #include "bts_device.h"
 
@@ -14,9 +19,8 @@ namespace {
 // KIND 1: dst = src                                   (1 read : 1 write)
 // KIND 2: dst = fma(alpha, src, dst)                  (2 reads : 1 write, the worker stage's mix)
 template <int KIND>
-__global__ __launch_bounds__(kStreamBlock) void k_probe(const float* __restrict__ src,
-                                                        float* __restrict__ dst, uint64_t n,
-                                                        float alpha) {
+__device__ __forceinline__ void probe_body(const float* __restrict__ src,
+                                           float* __restrict__ dst, uint64_t n, float alpha) {
   const uint64_t wc = (uint64_t)blockIdx.x * kStreamWaves + threadIdx.x / kWave;
   const uint64_t base = wc * kWaveChunk;
   if (base + kWaveChunk > n) return;                       // whole chunks only
@@ -45,28 +49,71 @@ __global__ __launch_bounds__(kStreamBlock) void k_probe(const float* __restrict_
   if (KIND == 0 && sum != sum) dst[0] = sum;
 }
 
+template <int KIND>
+__global__ __launch_bounds__(kStreamBlock) void k_probe(const float* __restrict__ src,
+                                                        float* __restrict__ dst, uint64_t n,
+                                                        float alpha) {
+  probe_body<KIND>(src, dst, n, alpha);
+}
+
+// The same stream held to WPS waves per SIMD (4 SIMDs per compute unit) by the compiler:
+// it sizes the kernel's register allocation so that no more fit.
+template <int KIND, int WPS>
+__global__ __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_eu(1, WPS))) void
+k_probe_held(const float* __restrict__ src, float* __restrict__ dst, uint64_t n, float alpha) {
+  probe_body<KIND>(src, dst, n, alpha);
+}
+
+template <int KIND>
+void launch(dim3 grid, dim3 block, int waves_per_cu, bool by_registers, hipStream_t s,
+            const float* src, float* dst, uint64_t n, float alpha) {
+  if (waves_per_cu == 0) {
+    k_probe<KIND><<<grid, block, 0, s>>>(src, dst, n, alpha);
+  } else if (by_registers) {
+    if (waves_per_cu == 12) k_probe_held<KIND, 3><<<grid, block, 0, s>>>(src, dst, n, alpha);
+    if (waves_per_cu == 20) k_probe_held<KIND, 5><<<grid, block, 0, s>>>(src, dst, n, alpha);
+    if (waves_per_cu == 24) k_probe_held<KIND, 6><<<grid, block, 0, s>>>(src, dst, n, alpha);
+  } else {
+    // workgroups of kStreamWaves waves; a compute unit has 160 KB of LDS
+    const uint32_t groups = (uint32_t)waves_per_cu / kStreamWaves;
+    const uint32_t lds = (163840u / groups) / 512u * 512u;
+    k_probe<KIND><<<grid, block, lds, s>>>(src, dst, n, alpha);
+  }
+}
+
 }  // namespace
 
-hipError_t hbm_probe(hipStream_t s, int kind, const float* src, float* dst, uint64_t n,
-                     float alpha, int repeats, double* ms_per_launch) {
+}  // namespace bts
+
+using namespace bts;
+
+extern "C" int bts_hbm_probe(void* hip_stream, int kind, const float* src, float* dst,
+                             uint64_t n, int waves_per_cu, int by_registers, int repeats,
+                             double* ms_per_launch) {
+  if (!src || !dst || !ms_per_launch || kind < 0 || kind > 2 || repeats < 1 || n < 512)
+    return -1;
+  if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u))
+    return -1;
+  if (waves_per_cu != 0 && waves_per_cu != 12 && waves_per_cu != 20 && waves_per_cu != 24)
+    return -1;
   const uint64_t chunks = n / kWaveChunk;
-  if (chunks == 0 || chunks / kStreamWaves + 1 > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  if (chunks / kStreamWaves + 1 > 0x7FFFFFFFull) return -1;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   const dim3 grid((unsigned)((chunks + kStreamWaves - 1) / kStreamWaves)), block(kStreamBlock);
-  const size_t lds = kind == 2 ? kMixedStreamLds : 0;     // as the dominant kernel is launched
   hipEvent_t e0, e1;
   hipError_t e = hipEventCreate(&e0);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess) return -1000 - (int)e;
   e = hipEventCreate(&e1);
   if (e != hipSuccess) {
     (void)hipEventDestroy(e0);
-    return e;
+    return -1000 - (int)e;
   }
   for (int it = -1; it < repeats && e == hipSuccess; ++it) {     // one untimed launch first
     if (it == 0) e = hipEventRecord(e0, s);
     if (e != hipSuccess) break;
-    if (kind == 0) k_probe<0><<<grid, block, lds, s>>>(src, dst, n, alpha);
-    if (kind == 1) k_probe<1><<<grid, block, lds, s>>>(src, dst, n, alpha);
-    if (kind == 2) k_probe<2><<<grid, block, lds, s>>>(src, dst, n, alpha);
+    if (kind == 0) launch<0>(grid, block, waves_per_cu, by_registers != 0, s, src, dst, n, 0.5f);
+    if (kind == 1) launch<1>(grid, block, waves_per_cu, by_registers != 0, s, src, dst, n, 0.5f);
+    if (kind == 2) launch<2>(grid, block, waves_per_cu, by_registers != 0, s, src, dst, n, 0.5f);
     e = hipGetLastError();
   }
   if (e == hipSuccess) e = hipEventRecord(e1, s);
@@ -75,8 +122,7 @@ hipError_t hbm_probe(hipStream_t s, int kind, const float* src, float* dst, uint
   if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
-  if (e == hipSuccess) *ms_per_launch = (double)ms / repeats;
-  return e;
+  if (e != hipSuccess) return -1000 - (int)e;
+  *ms_per_launch = (double)ms / repeats;
+  return 0;
 }
-
-}  // namespace bts

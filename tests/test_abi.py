@@ -9,12 +9,10 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "bts.h")).read()
+def declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"^\s*(?:int|void|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
-    assert len(names) >= 10
-    return names
+    return re.findall(r"^\s*(?:int|void|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
 
 
 @pytest.fixture(scope="module")
@@ -27,11 +25,23 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
+    """The contract (bts.h), the testing aids (bts_testing.h) and the measurement instrument
+    (bts_probe.h, a library of its own): each library exports exactly what its header
+    declares, and the binding lists the same names."""
     from paper_2209_15203_amd import binding
-    names = declared_symbols()
-    for n in names:
+    contract = declared_symbols("bts.h")
+    aids = declared_symbols("bts_testing.h")
+    probe = declared_symbols("bts_probe.h")
+    assert len(contract) >= 11 and len(aids) >= 5 and probe == ["bts_hbm_probe"]
+    for n in contract + aids:
         assert hasattr(lib, n), n
-    assert sorted(names) == sorted(binding.EXPORTS)
+    assert sorted(contract) == sorted(binding.EXPORTS)
+    assert sorted(aids) == sorted(binding.TESTING_EXPORTS)
+    plib = binding.load_probe_library()
+    for n in probe:
+        assert hasattr(plib, n), n
+    assert probe == binding.PROBE_EXPORTS
+    assert not hasattr(lib, "bts_hbm_probe"), "the probe is not part of the product library"
 
 
 def test_create_rejects_bad_shapes_without_a_gpu(lib):
@@ -63,9 +73,10 @@ def test_missing_library_fails_loudly(monkeypatch):
 
 
 def test_header_is_plain_c(tmp_path):
-    """The boundary is a C ABI: the header must compile as C99 without any HIP or C++."""
+    """The boundary is a C ABI: the headers must compile as C99 without any HIP or C++."""
     import subprocess
     src = tmp_path / "t.c"
-    src.write_text('#include "bts.h"\nint main(void) { return BTS_OK; }\n')
+    src.write_text('#include "bts.h"\n#include "bts_testing.h"\n#include "bts_probe.h"\n'
+                   'int main(void) { return BTS_OK; }\n')
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
                     "-I", os.path.join(ROOT, "include"), "-fsyntax-only", str(src)], check=True)

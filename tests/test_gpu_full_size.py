@@ -16,6 +16,17 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture
+def say(capsys):
+    """Progress lines that reach the terminal while output is captured: a step of the
+    largest configuration takes the oracle most of a minute, and a run that stays silent
+    for minutes is taken to be hung."""
+    def _say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+    return _say
+
+
 def assert_rows_same_bits(got: torch.Tensor, want: np.ndarray, what: str):
     """got (device, 2-D) against want (host, 2-D) as uint32 words, one row at a time on the
     device (a row of the largest configuration is 440 MB; the whole matrix 28 GB)."""
@@ -31,7 +42,7 @@ def assert_rows_same_bits(got: torch.Tensor, want: np.ndarray, what: str):
                 f"0x{int(ref[i]) & 0xFFFFFFFF:08x}")
 
 
-def run_full_size(oracle, name, alpha_in, alpha_out):
+def run_full_size(oracle, name, alpha_in, alpha_out, say):
     import _gpu_util as G
     import paper_2209_15203_amd as bts
     cfg = wl.CONFIGS[name]
@@ -60,8 +71,7 @@ def run_full_size(oracle, name, alpha_in, alpha_out):
     for t in range(1, cfg.steps + 1):
         src.fill(t, g)
         tag = f"{name} step {t}"
-        print(f"[{name}] step {t}/{cfg.steps} at {time.perf_counter() - t_start:.0f} s",
-              flush=True)
+        say(f"[{name}] step {t}/{cfg.steps} at {time.perf_counter() - t_start:.0f} s")
         bts.bidir_step(ctx, g, eps, delta, w, p, alpha_in, alpha_out, ui, uv, di, dv, nnz)
         torch.cuda.synchronize()
         torch.from_numpy(h_g).copy_(g)           # straight into the oracle's input buffer
@@ -75,22 +85,21 @@ def run_full_size(oracle, name, alpha_in, alpha_out):
         G.assert_same_bits(delta, h_delta, f"{tag} delta")
         G.assert_same_bits(w, h_w, f"{tag} w")
         assert int(nnz.item()) == want["union_nnz"], f"{tag} union nnz"
-    print(f"[{name}] {cfg.steps} steps compared in {time.perf_counter() - t_start:.0f} s",
-          flush=True)
+    say(f"[{name}] {cfg.steps} steps compared in {time.perf_counter() - t_start:.0f} s")
 
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
-def test_full_size_config(oracle, name):
+def test_full_size_config(oracle, name, say):
     """Paper form: the step size inside a (alpha_in = alpha, alpha_out = 1)."""
-    run_full_size(oracle, name, wl.CONFIGS[name].alpha, 1.0)
+    run_full_size(oracle, name, wl.CONFIGS[name].alpha, 1.0, say)
 
 
 @pytest.mark.timeout(600)
-def test_full_size_other_alpha_form_c2(oracle):
+def test_full_size_other_alpha_form_c2(oracle, say):
     """The other placement of the step size (alpha_in = 1, alpha_out = alpha: residual added
     to the raw gradient, w -= alpha * message) at a benchmark size: C2, every step."""
-    run_full_size(oracle, "C2", 1.0, wl.CONFIGS["C2"].alpha)
+    run_full_size(oracle, "C2", 1.0, wl.CONFIGS["C2"].alpha, say)
 
 
 @pytest.mark.timeout(600)
