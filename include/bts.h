@@ -43,6 +43,9 @@ extern "C" {
                         /* N > 65535, or a dense buffer (g, eps, delta) not 16-byte aligned */
 #define BTS_ENOMEM (-2) /* scratch allocation failed                                       */
 #define BTS_EHIP (-3)   /* a HIP call failed; see bts_last_hip_error                       */
+#define BTS_ELIMIT (-4) /* shape beyond the fixed scratch of topk_compress_noalloc         */
+#define BTS_EHIP_BASE (-1000) /* topk_compress_noalloc only: a HIP call failed with        */
+                              /* hipError_t e; the call returns BTS_EHIP_BASE - e           */
 
 typedef struct bts_ctx bts_ctx;
 
@@ -74,6 +77,24 @@ int bts_last_hip_error(const bts_ctx* ctx);
  */
 int topk_compress(bts_ctx* ctx, const float* g, float* eps, float alpha_in, uint32_t* up_idx,
                   float* up_val);
+
+/*
+ * For callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same operation and same results as
+ * topk_compress (g, eps, alpha_in, up_idx, up_val as there), but without a context: the
+ * shape travels in the call, the work is queued on hip_stream (a hipStream_t, host value,
+ * borrowed, null = the default stream; it must belong to the current device), and the
+ * select's scratch lives in a fixed 13 MiB array that each GPU the library runs on holds
+ * until the process ends.  The call makes no hipMalloc, hipFree or other allocating call;
+ * its first call on a device looks up that device's copy of the array.
+ * Limits: N <= 256 and N * (ceil(d / 512) + 1) <= 2^20 (about 5.3e8 coordinates per call);
+ * beyond them the call returns BTS_ELIMIT and queues nothing.  A failed HIP call returns
+ * BTS_EHIP_BASE - hipError_t.  All calls on one GPU share that GPU's array: calls that
+ * overlap on one GPU (two streams, two threads) race and must be serialised by the caller;
+ * calls that follow each other on one stream are safe, whatever their shapes.
+ */
+int topk_compress_noalloc(const float* g, float* eps, int32_t N, uint64_t d, uint32_t K_up,
+                          float alpha_in, uint32_t* up_idx, float* up_val, void* hip_stream);
 
 /*
  * Server aggregation line of Algorithm 2:  g_t = sum_q p_q Top_K(a^q) + delta_{t-1}.

@@ -7,7 +7,8 @@ no CPU fallback: importing :mod:`paper_2209_15203_amd.binding` without the built
 fails loudly.
 """
 from .binding import (BtsContext, BtsError, bidir_step, bidir_step_diag, downlink_topk, lib_path, load_library,
-                      sparse_aggregate, sparse_sgd_update, topk_compress, unidir_step)
+                      sparse_aggregate, sparse_sgd_update, topk_compress, topk_compress_noalloc,
+                      unidir_step)
 
 __all__ = ["BtsContext", "BtsError", "bidir_step", "bidir_step_diag", "downlink_topk", "lib_path", "load_library",
-           "sparse_aggregate", "sparse_sgd_update", "topk_compress", "unidir_step"]
+           "sparse_aggregate", "sparse_sgd_update", "topk_compress", "topk_compress_noalloc", "unidir_step"]

@@ -11,6 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libbts.so")
 
 EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
+           "topk_compress_noalloc",
            "sparse_aggregate", "downlink_topk", "sparse_sgd_update", "bidir_step",
            "unidir_step", "bts_enable_diagnostics", "bidir_step_diag"]
 # testing and measurement aids of the same library (include/bts_testing.h)
@@ -48,6 +49,7 @@ def load_library():
     lib.bts_destroy.restype = None
     lib.bts_last_hip_error.argtypes = [vp]
     lib.topk_compress.argtypes = [vp, vp, vp, f32, vp, vp]
+    lib.topk_compress_noalloc.argtypes = [vp, vp, i32, u64, u32, f32, vp, vp, vp]
     lib.sparse_aggregate.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.downlink_topk.argtypes = [vp, vp, vp, vp]
     lib.sparse_sgd_update.argtypes = [vp, vp, vp, u32, f32, vp]
@@ -96,7 +98,7 @@ def hbm_probe(kind: int, src: torch.Tensor, dst: torch.Tensor, waves_per_cu: int
     return ms.value
 
 
-_CODES = {-1: "BTS_EINVAL", -2: "BTS_ENOMEM", -3: "BTS_EHIP"}
+_CODES = {-1: "BTS_EINVAL", -2: "BTS_ENOMEM", -3: "BTS_EHIP", -4: "BTS_ELIMIT"}
 
 
 def _ptr(t: Optional[torch.Tensor], dtype, name: str, numel: Optional[int] = None):
@@ -182,6 +184,22 @@ def topk_compress(ctx: BtsContext, g, eps, alpha_in: float, up_idx, up_val) -> N
     ctx.check(ctx._lib.topk_compress(ctx._h, _ptr(g, F32, "g", nd), _ptr(eps, F32, "eps", nd),
                                      alpha_in, _ptr(up_idx, U32, "up_idx", nk),
                                      _ptr(up_val, F32, "up_val", nk)), "topk_compress")
+
+
+def topk_compress_noalloc(g, eps, alpha_in: float, up_idx, up_val,
+                          stream: Optional[torch.cuda.Stream] = None) -> None:
+    """topk_compress without a context and without any allocation (fixed scratch, bounded
+    shapes); the shape is taken from g (N x d) and up_idx (N x K_up)."""
+    N, d = g.shape
+    K_up = 0 if up_idx is None else up_idx.shape[1]
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = load_library().topk_compress_noalloc(
+        _ptr(g, F32, "g", N * d), _ptr(eps, F32, "eps", N * d), N, d, K_up, alpha_in,
+        _ptr(up_idx, U32, "up_idx", N * K_up), _ptr(up_val, F32, "up_val", N * K_up),
+        C.c_void_p(st.cuda_stream))
+    if rc != 0:
+        what = _CODES.get(rc, f"hip error {-1000 - rc}" if rc <= -1000 else rc)
+        raise BtsError(f"topk_compress_noalloc failed: {what}")
 
 
 def sparse_aggregate(ctx: BtsContext, up_idx, up_val, p, delta, union_nnz=None) -> None:

@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(lib):
     contract = declared_symbols("bts.h")
     aids = declared_symbols("bts_testing.h")
     probe = declared_symbols("bts_probe.h")
-    assert len(contract) >= 11 and len(aids) >= 5 and probe == ["bts_hbm_probe"]
+    assert len(contract) >= 12 and len(aids) >= 5 and probe == ["bts_hbm_probe"]
     for n in contract + aids:
         assert hasattr(lib, n), n
     assert sorted(contract) == sorted(binding.EXPORTS)

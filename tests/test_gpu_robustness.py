@@ -117,6 +117,8 @@ def test_binding_refuses_undersized_tensors():
     with pytest.raises(TypeError):
         bts.unidir_step(ctx, good["g"], good["eps"], good["w"], good["p"], 0.01, 1.0,
                         good["up_idx"], good["up_val"], i(N * K - 1), f(N * K - 1), i(1))
+    with pytest.raises(TypeError):
+        bts.topk_compress_noalloc(good["g"], f(N, d - 1), 0.01, good["up_idx"], good["up_val"])
     bts.bidir_step(ctx, *(good[k] for k in ("g", "eps", "delta", "w", "p")), 0.01, 1.0,
                    *(good[k] for k in ("up_idx", "up_val", "dn_idx", "dn_val")))
     torch.cuda.synchronize()
