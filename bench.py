@@ -306,6 +306,11 @@ def main() -> int:
                 tag = name if waves == 0 else f"{name}_{waves}waves_{'regs' if by_regs else 'lds'}"
                 out[tag] = {"ms": ms, "gbps": bytes_per * n / ms / 1e6,
                             "frac_of_peak": bytes_per * n / ms / 1e6 / HBM_PEAK_GBS}
+        # the fma-stream at 12 waves with plain (cached) instead of non-temporal accesses
+        for code, tag in ((101, "plain_loads"), (102, "plain_stores"), (103, "plain_both")):
+            ms = binding.hbm_probe(2, src_p, dst_p, code, True, repeats=max(1, args.steps))
+            out[f"fma_stream_12waves_{tag}"] = {"ms": ms, "gbps": 12 * n / ms / 1e6,
+                                                "frac_of_peak": 12 * n / ms / 1e6 / HBM_PEAK_GBS}
         print(json.dumps(out))
         return 0
 

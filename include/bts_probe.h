@@ -20,7 +20,9 @@ extern "C" {
  * waves_per_cu: 0 = every wave slot may fill; 12, 20 or 24 = the launch is held to that
  * many waves per compute unit, by_registers == 0: through dynamic LDS it requests and
  * never touches; by_registers != 0: through the register allocation of a kernel variant
- * compiled for at most that many waves per SIMD.
+ * compiled for at most that many waves per SIMD.  With kind 2 only, waves_per_cu = 101, 102,
+ * 103: the fma-stream at 12 waves per compute unit with plain instead of non-temporal
+ * accesses (101 the loads, 102 the stores, 103 both).
  * Queues one untimed launch and `repeats` timed ones on hip_stream (a hipStream_t, host
  * value, null = default stream), waits for them, and returns the mean time of one launch
  * in milliseconds (host pointer).  kinds 1 and 2 overwrite dst.

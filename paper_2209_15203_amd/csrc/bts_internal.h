@@ -12,11 +12,6 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kUnroll = 2;                // float4 loads in flight per lane and array
 constexpr int kStreamBlock = 128;         // threads per workgroup of the dominant kernel
 constexpr int kStreamWaves = kStreamBlock / kWave;
-// Dynamic LDS requested (and never touched) by a plain stream of 2 reads : 1 write over
-// N x d, only to hold it to 6 workgroups = 12 waves per compute unit: with every wave slot
-// filled the mix of reads and writes reaches 6.2 TB/s, at 12 waves 6.4 (13.3 against 13.7 ms
-// at N x d = 7.04e9; 8 waves are slower again, and so are read-only streams under any cap).
-constexpr uint32_t kMixedStreamLds = 24576;
 // A wave owns kWaveChunk consecutive coordinates (absolute, 16-byte aligned offsets).
 constexpr uint32_t kWaveChunk = kWave * 4 * kUnroll;   
 constexpr int kBins0 = 2048;              // first digit: key bits 30..20
@@ -86,7 +81,7 @@ struct FastPlan {
   uint32_t stride;         // every stride-th 256-coordinate slice is sampled
   uint32_t target;         // sampled coordinates wanted at or above the lower bound
   uint32_t cap;            // capacity of one candidate list
-  uint32_t stream_lds;     // dynamic LDS of the dense pass (limits its waves per compute unit)
+  uint32_t stream_waves_per_simd;   // occupancy the dense pass is held to (3, 5 or 6)
   uint32_t ntiles;         // directory tiles (64 wave chunks) per row
   uint32_t nwc_pad;        // directory entries per row (ntiles * 64)
 };

@@ -216,7 +216,7 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 }
 
 template <bool FMA, bool ENERGY>
-__global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
+__device__ __forceinline__ void stream_capture_body(
     const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
     const uint32_t* __restrict__ lower_key, uint32_t* __restrict__ cand_cnt,
     uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir, uint32_t nwc_pad,
@@ -285,6 +285,22 @@ __global__ __launch_bounds__(kStreamBlock) void k_stream_capture(
     if (lane_id() == 0) energy[(uint64_t)row * nwc_pad + wc] = e;
   }
   append_run(flags, v, i0, counter, list, cap, dir_entry);
+}
+
+// WPS: the most waves per SIMD (four SIMDs per compute unit) the kernel may run with; the
+// compiler sizes the kernel's register allocation so that no more fit (kMaxWavesPerSimd =
+// no limit).  A stream of 2 reads : 1 write runs best well below full occupancy, see
+// fast_plan.
+constexpr int kMaxWavesPerSimd = 8;
+
+template <bool FMA, bool ENERGY, int WPS>
+__global__ __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_eu(1, WPS))) void
+k_stream_capture(const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
+                 const uint32_t* __restrict__ lower_key, uint32_t* __restrict__ cand_cnt,
+                 uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir,
+                 uint32_t nwc_pad, double* __restrict__ energy) {
+  stream_capture_body<FMA, ENERGY>(g, x, d, alpha, lower_key, cand_cnt, cand, cap, dir, nwc_pad,
+                                   energy);
 }
 
 // ---- 3 + 4. verify and select on the candidate lists -------------------------------------
@@ -740,15 +756,16 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.stride = (uint32_t)stride;
   p.target = (uint32_t)target;
   p.cap = (uint32_t)cap;
-  // How many waves per compute unit the dense pass is held to (through LDS it requests and
-  // never touches): a stream of 2 reads : 1 write runs best well below full occupancy, but a
-  // wave whose chunk has hits waits for its append, and the more chunks have hits the more
-  // waves it takes to hide that.  About 3K candidates over d / kWaveChunk chunks.  Measured
-  // per launch: 13.3 against 13.7 ms at C5 (0.15 per chunk, 12 waves), 1.545 against 1.58 ms
-  // at C3 (1.5 per chunk, 20 waves; 12 waves: 1.67 ms), 0.342 against 0.346 ms at C2 (15
-  // per chunk, 26 waves).
+  // How many waves per SIMD the dense pass is held to (a kernel variant whose register
+  // allocation admits no more): a stream of 2 reads : 1 write runs best well below full
+  // occupancy, but a wave whose chunk has hits waits for its append, and the more chunks
+  // have hits the more waves it takes to hide that.  About 3K candidates over
+  // d / kWaveChunk chunks.  Measured per launch: 13.3 against 13.7 ms at 7e9 coordinates
+  // (0.15 candidates per chunk, 3 waves per SIMD = 12 per compute unit), 1.545 against
+  // 1.58 ms at 8e8 (1.5 per chunk, 5 per SIMD; 3 per SIMD: 1.67 ms), 0.342 against
+  // 0.346 ms at 1.8e8 (15 per chunk, 6 per SIMD).
   const uint64_t per_chunk_x10 = 30ull * K * kWaveChunk / d;
-  p.stream_lds = per_chunk_x10 < 5 ? kMixedStreamLds : (per_chunk_x10 < 50 ? 16384u : 12288u);
+  p.stream_waves_per_simd = per_chunk_x10 < 5 ? 3u : (per_chunk_x10 < 50 ? 5u : 6u);
   p.ntiles = (uint32_t)(((d + kWaveChunk - 1) / kWaveChunk + 1 + kTileChunks - 1) / kTileChunks);
   p.nwc_pad = p.ntiles * kTileChunks;
   return p;
@@ -789,17 +806,21 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   // 2. the dense pass (a wave of the grid may lie past the row's last chunk, never past
   // the padded directory)
   if (ev0) (void)hipEventRecord(ev0, s);
-  if (g != nullptr && energy)
-    k_stream_capture<true, true><<<dense_grid, dim3(kStreamBlock), pl.stream_lds, s>>>(
-        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad,
-        sc.energy);
-  else if (g != nullptr)
-    k_stream_capture<true, false><<<dense_grid, dim3(kStreamBlock), pl.stream_lds, s>>>(
-        g, x, d, alpha, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad, nullptr);
-  else
-    k_stream_capture<false, false><<<dense_grid, dim3(kStreamBlock), 0, s>>>(
-        nullptr, x, d, 0.0f, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad,
-        nullptr);
+#define BTS_CAPTURE(FMA, ENERGY, WPS, G, ALPHA, EN)                                        \
+  k_stream_capture<FMA, ENERGY, WPS><<<dense_grid, dim3(kStreamBlock), 0, s>>>(            \
+      G, x, d, ALPHA, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad, EN)
+  if (g == nullptr) {
+    BTS_CAPTURE(false, false, kMaxWavesPerSimd, nullptr, 0.0f, nullptr);
+  } else if (energy) {
+    if (pl.stream_waves_per_simd == 3) BTS_CAPTURE(true, true, 3, g, alpha, sc.energy);
+    else if (pl.stream_waves_per_simd == 5) BTS_CAPTURE(true, true, 5, g, alpha, sc.energy);
+    else BTS_CAPTURE(true, true, 6, g, alpha, sc.energy);
+  } else {
+    if (pl.stream_waves_per_simd == 3) BTS_CAPTURE(true, false, 3, g, alpha, nullptr);
+    else if (pl.stream_waves_per_simd == 5) BTS_CAPTURE(true, false, 5, g, alpha, nullptr);
+    else BTS_CAPTURE(true, false, 6, g, alpha, nullptr);
+  }
+#undef BTS_CAPTURE
   BTS_LAUNCH_CHECK();
   if (ev1) (void)hipEventRecord(ev1, s);
   // 3 + 4. verify and select: a few fat blocks per row, each taking whole lists (about 32768

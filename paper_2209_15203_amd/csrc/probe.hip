@@ -18,7 +18,8 @@ namespace {
 // KIND 0: read src (a word is stored only if a sum of loaded values is NaN, so the loads stay)
 // KIND 1: dst = src                                   (1 read : 1 write)
 // KIND 2: dst = fma(alpha, src, dst)                  (2 reads : 1 write, the worker stage's mix)
-template <int KIND>
+// CACHED bit 0: plain loads instead of non-temporal ones; bit 1: plain stores.
+template <int KIND, int CACHED = 0>
 __device__ __forceinline__ void probe_body(const float* __restrict__ src,
                                            float* __restrict__ dst, uint64_t n, float alpha) {
   const uint64_t wc = (uint64_t)blockIdx.x * kStreamWaves + threadIdx.x / kWave;
@@ -29,8 +30,11 @@ __device__ __forceinline__ void probe_body(const float* __restrict__ src,
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint64_t e = e0 + (uint64_t)u * (kWave * 4);
-    a[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(src + e));
-    if (KIND == 2) b[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(dst + e));
+    a[u] = (CACHED & 1) ? *reinterpret_cast<const f4*>(src + e)
+                        : __builtin_nontemporal_load(reinterpret_cast<const f4*>(src + e));
+    if (KIND == 2)
+      b[u] = (CACHED & 1) ? *reinterpret_cast<const f4*>(dst + e)
+                          : __builtin_nontemporal_load(reinterpret_cast<const f4*>(dst + e));
   }
   float sum = 0.0f;
 #pragma unroll
@@ -43,7 +47,10 @@ __device__ __forceinline__ void probe_body(const float* __restrict__ src,
       b[u].y = __fmaf_rn(alpha, a[u].y, b[u].y);
       b[u].z = __fmaf_rn(alpha, a[u].z, b[u].z);
       b[u].w = __fmaf_rn(alpha, a[u].w, b[u].w);
-      __builtin_nontemporal_store(b[u], reinterpret_cast<f4*>(dst + e));
+      if (CACHED & 2)
+        *reinterpret_cast<f4*>(dst + e) = b[u];
+      else
+        __builtin_nontemporal_store(b[u], reinterpret_cast<f4*>(dst + e));
     }
   }
   if (KIND == 0 && sum != sum) dst[0] = sum;
@@ -64,10 +71,21 @@ k_probe_held(const float* __restrict__ src, float* __restrict__ dst, uint64_t n,
   probe_body<KIND>(src, dst, n, alpha);
 }
 
+// The fma-stream at 12 waves per compute unit with plain (cached) loads and/or stores.
+template <int CACHED>
+__global__ __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_eu(1, 3))) void
+k_probe_cached(const float* __restrict__ src, float* __restrict__ dst, uint64_t n, float alpha) {
+  probe_body<2, CACHED>(src, dst, n, alpha);
+}
+
 template <int KIND>
 void launch(dim3 grid, dim3 block, int waves_per_cu, bool by_registers, hipStream_t s,
             const float* src, float* dst, uint64_t n, float alpha) {
-  if (waves_per_cu == 0) {
+  if (waves_per_cu >= 100) {                 // 101..103: the cached variants of kind 2
+    if (waves_per_cu == 101) k_probe_cached<1><<<grid, block, 0, s>>>(src, dst, n, alpha);
+    if (waves_per_cu == 102) k_probe_cached<2><<<grid, block, 0, s>>>(src, dst, n, alpha);
+    if (waves_per_cu == 103) k_probe_cached<3><<<grid, block, 0, s>>>(src, dst, n, alpha);
+  } else if (waves_per_cu == 0) {
     k_probe<KIND><<<grid, block, 0, s>>>(src, dst, n, alpha);
   } else if (by_registers) {
     if (waves_per_cu == 12) k_probe_held<KIND, 3><<<grid, block, 0, s>>>(src, dst, n, alpha);
@@ -94,7 +112,9 @@ extern "C" int bts_hbm_probe(void* hip_stream, int kind, const float* src, float
     return -1;
   if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u))
     return -1;
-  if (waves_per_cu != 0 && waves_per_cu != 12 && waves_per_cu != 20 && waves_per_cu != 24)
+  const bool cached_variant = kind == 2 && waves_per_cu >= 101 && waves_per_cu <= 103;
+  if (waves_per_cu != 0 && waves_per_cu != 12 && waves_per_cu != 20 && waves_per_cu != 24 &&
+      !cached_variant)
     return -1;
   const uint64_t chunks = n / kWaveChunk;
   if (chunks / kStreamWaves + 1 > 0x7FFFFFFFull) return -1;
