@@ -189,9 +189,10 @@ def main() -> int:
                     help="no GPU work: write the workload's entry of profiles/traffic.json from "
                          "the counter_collection.csv files of two rocprofv3 --pmc runs "
                          "(FETCH_SIZE, WRITE_SIZE) of this script with --calibrate-copy")
-    ap.add_argument("--path", choices=["auto", "dense", "single"], default="auto",
-                    help="select path: chosen by shape (default), dense multi-pass only, or "
-                         "single-pass wherever the shape allows")
+    ap.add_argument("--path", choices=["auto", "dense", "single", "three"], default="auto",
+                    help="select path: chosen by shape (default), dense multi-pass only, "
+                         "single-pass wherever the shape allows, or the three-launch select "
+                         "wherever the shape allows")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -237,7 +238,7 @@ def main() -> int:
 
     side = torch.cuda.Stream(device=dev) if args.graph else None
     ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn, stream=side)
-    ctx.set_path({"auto": 0, "dense": 1, "single": 2}[args.path])
+    ctx.set_path({"auto": 0, "dense": 1, "single": 2, "three": 3}[args.path])
     eps = torch.zeros((N, d), dtype=torch.float32, device=dev)
     delta = torch.zeros(d, dtype=torch.float32, device=dev)
     w = wl.weights0(cfg, dev)

@@ -25,16 +25,19 @@ int bts_profile_read(bts_ctx* ctx, double* ms_total, uint64_t* launches);
 
 /* Path taken by the last topk_compress / downlink_topk on this context, for tests and
  * reports: a host-synchronous read of per-row flags.  rows_fast = rows finished by the
- * single-pass path, rows_dense = all others (dense multi-pass path, or the one-workgroup
- * path of short rows); rows_fast + rows_dense == rows.  which: 0 = uplink, 1 = downlink. */
+ * single-pass path, rows_dense = all others (dense multi-pass path, the three-launch path of
+ * middling rows, or the one-workgroup path of short rows); rows_fast + rows_dense == rows.
+ * which: 0 = uplink, 1 = downlink. */
 int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_dense);
 
 /* Testing aid: which select path later calls on this context take.  0 (default): chosen
- * by shape (one workgroup per row up to d = 8192, else dense multi-pass, else single-pass
- * from about 1.1e7 coordinates per call, 2.5e7 for a single row); 1: the dense multi-pass
- * path only (the path that also serves as the fallback); 2: the single-pass path wherever
- * the shape allows it (d >= 65536 and K <= d/64), whatever its size.  Results are identical
- * in every mode. */
+ * by shape (one workgroup per row up to d = 8192; the three-launch select for K <= 8192,
+ * K <= d/64 on rows up to 2^22 coordinates where the call is bound by its launches; the
+ * single-pass select from about 1.1e7 coordinates per call, 2.5e7 for a single row; else the
+ * dense multi-pass select); 1: the dense multi-pass path only (the path that also serves as
+ * the fallback); 2: the single-pass path wherever the shape allows it (d >= 65536 and
+ * K <= d/64), whatever its size; 3: the three-launch path wherever the shape allows it.
+ * Results are identical in every mode. */
 int bts_set_path(bts_ctx* ctx, int mode);
 
 /* Testing aid: makes the next calls on this context behave as after a call that failed

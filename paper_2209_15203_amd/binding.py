@@ -163,7 +163,8 @@ class BtsContext:
         self.check(self._lib.bts_enable_diagnostics(self._h), "bts_enable_diagnostics")
 
     def set_path(self, mode: int) -> None:
-        """0 = by shape, 1 = dense path only, 2 = single-pass path wherever possible."""
+        """0 = by shape, 1 = dense path only, 2 = single-pass path wherever possible,
+        3 = three-launch path wherever possible."""
         self.check(self._lib.bts_set_path(self._h, int(mode)), "bts_set_path")
 
     def testing_mark_dirty(self) -> None:

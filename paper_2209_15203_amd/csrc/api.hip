@@ -23,6 +23,9 @@ struct bts_ctx {
   bool fast_up_dirty, fast_dn_dirty;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
+  MidPlan mid_plan_up, mid_plan_dn;   // the three-launch select of middling rows with small K
+  MidScratch mid_up, mid_dn;
+  bool mid_up_dirty, mid_dn_dirty;
   FastPlan plan_diag_u;         // diagnostics: one row of length d with K_up (the select of
   FastScratch fast_diag_u;      //   sum_q p_q a^q); the one with K_dn reuses plan_dn / fast_dn
   bool fast_diag_u_dirty;
@@ -36,7 +39,8 @@ struct bts_ctx {
   std::vector<void*> owned;     // every device allocation of the context
   // timing of the dominant kernel
   bool profile;
-  int path_mode;                // 0 = by shape, 1 = dense only, 2 = single-pass where possible
+  int path_mode;                // 0 = by shape, 1 = dense only, 2 = single-pass where possible,
+                                // 3 = the three-launch select where possible
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;
   size_t ev_used;
 };
@@ -96,6 +100,19 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
   return ok;
 }
 
+bool alloc_mid(bts_ctx* ctx, const MidPlan& pl, uint32_t rows, MidScratch* sc) {
+  if (!pl.enabled) return true;
+  uint8_t* bound = nullptr;
+  bool ok = dev_alloc(ctx, &sc->hist, (size_t)rows * mid_hist_words()) &&
+            dev_alloc(ctx, &bound, (size_t)rows * mid_bound_bytes()) &&
+            dev_alloc(ctx, &sc->cand_cnt, (size_t)rows * fast_sublists() * fast_counter_stride()) &&
+            dev_alloc(ctx, &sc->cand, (size_t)rows * fast_sublists() * pl.cap) &&
+            dev_alloc(ctx, &sc->dir, (size_t)rows * pl.nwc_pad);
+  sc->bound = bound;
+  sc->rows = rows;
+  return ok;
+}
+
 // The entry/exit tables pay off when most ranges are empty for most workers; they are
 // skipped (binary search instead) when they would be large.
 bool alloc_agg_tables(bts_ctx* ctx) {
@@ -133,8 +150,15 @@ void profile_events(bts_ctx* ctx, hipEvent_t* e0, hipEvent_t* e1) {
   ctx->ev_used++;
 }
 
+// The three-launch select: where the shape allows it and, by default, prefers it (calls
+// bound by their launches, not by bytes); it is tried before the single-pass select.
+bool use_mid(const bts_ctx* ctx, const MidPlan& mp) {
+  if (!mp.enabled || ctx->path_mode == 1 || ctx->path_mode == 2) return false;
+  return ctx->path_mode == 3 || mp.preferred;
+}
+
 bool use_fast(const bts_ctx* ctx, const FastPlan& pl) {
-  if (!pl.enabled || ctx->path_mode == 1) return false;
+  if (!pl.enabled || ctx->path_mode == 1 || ctx->path_mode == 3) return false;
   return ctx->path_mode == 2 || pl.preferred;
 }
 
@@ -143,12 +167,20 @@ bool use_fast(const bts_ctx* ctx, const FastPlan& pl) {
 // (and every row where it is not enabled) go through the dense path.
 // energy (diagnostics, uplink only): the single-pass path also leaves the partial sums of the
 // rows' residual energies in its scratch; *energy is cleared if another path ran.
+// upd (downlink only): the model update done by the emitting lanes.
+// ranges (uplink only, nullable): in: the caller is about to aggregate exactly these
+// messages; out: the select has filled the aggregation's range tables for them.
 int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha, uint32_t* idx,
-               float* val, bool* energy = nullptr) {
+               float* val, bool* energy = nullptr,
+               FusedUpdate upd = FusedUpdate{nullptr, 0.0f}, bool* ranges = nullptr) {
   const uint32_t rows = uplink ? (uint32_t)ctx->N : 1u;
   const uint32_t K = uplink ? ctx->K_up : ctx->K_dn;
   const FastPlan& pl = uplink ? ctx->plan_up : ctx->plan_dn;
   const FastScratch& fs = uplink ? ctx->fast_up : ctx->fast_dn;
+  const MidPlan& mp = uplink ? ctx->mid_plan_up : ctx->mid_plan_dn;
+  const MidScratch& ms = uplink ? ctx->mid_up : ctx->mid_dn;
+  const bool want_ranges = ranges != nullptr && *ranges;
+  if (ranges != nullptr) *ranges = false;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (uplink) profile_events(ctx, &e0, &e1);
   hipError_t e;
@@ -158,15 +190,46 @@ int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha,
     if (g == nullptr) return BTS_OK;
     e = axpy_only(ctx->stream, g, x, rows, ctx->d, alpha, e0, e1);
   } else if (ctx->path_mode == 0 && row_select_fits(ctx->d)) {
-    e = row_select(ctx->stream, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1);
+    e = row_select(ctx->stream, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1, upd);
+  } else if (use_mid(ctx, mp)) {
+    MidRanges mr{nullptr, nullptr, nullptr};
+    const AggScratch as = agg_scratch(ctx);
+    if (want_ranges && as.tab_start != nullptr) {
+      mr = MidRanges{as.tab_start, as.tab_end, as.any};
+      *ranges = true;
+    }
+    e = mid_select(ctx->stream, ms, mp, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1, upd, mr);
   } else if (use_fast(ctx, pl)) {
     e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1,
-                    ctx->dense, want_energy);
+                    ctx->dense, want_energy, upd);
     if (energy != nullptr) *energy = want_energy;
   } else {
     e = dense_select(ctx->stream, ctx->dense, g, x, rows, ctx->d, K, alpha, idx, val, nullptr,
-                     false, e0, e1);
+                     false, e0, e1, upd);
   }
+  return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
+}
+
+// Server compression and model update lines of Algorithm 2.  For a short message the lane
+// that emits a pair also applies it to w (same result as downlink_topk followed by
+// sparse_sgd_update, one kernel launch less).  The update reads w at a scattered address, and
+// an emitting wave does its pairs one after the other: from a few thousand pairs on, the
+// update kernel of its own (one pair per thread, all loads in flight at once) is quicker than
+// the launch it costs (at K_dn = 111,740 the fused emission took 43 us against 20 + 6).
+int downlink_and_update(bts_ctx* ctx, float* delta, uint32_t* dn_idx, float* dn_val,
+                        float alpha_out, float* w) {
+  if (ctx->K_dn <= 4096)
+    return run_select(ctx, false, nullptr, delta, 0.0f, dn_idx, dn_val, nullptr,
+                      FusedUpdate{w, -alpha_out});
+  const int rc = run_select(ctx, false, nullptr, delta, 0.0f, dn_idx, dn_val);
+  if (rc != BTS_OK) return rc;
+  return sparse_sgd_update(ctx, dn_idx, dn_val, ctx->K_dn, alpha_out, w);
+}
+
+int aggregate_messages(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, const float* p,
+                       float* delta, uint32_t* union_nnz, bool ranges_ready) {
+  hipError_t e = aggregate(ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, delta,
+                           ctx->d, union_nnz, agg_scratch(ctx), ranges_ready);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -210,6 +273,9 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->fast_dn = FastScratch{};
   ctx->fast_diag_u = FastScratch{};
   ctx->plan_diag_u = FastPlan{};
+  ctx->mid_up = MidScratch{};
+  ctx->mid_dn = MidScratch{};
+  ctx->mid_up_dirty = ctx->mid_dn_dirty = false;
   ctx->agg_ranges = nullptr;
   ctx->diag = DiagScratch{};
   ctx->diag_ready = false;
@@ -227,11 +293,12 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->dense.dirty = &ctx->dense_dirty;
   ctx->plan_up = fast_plan(rows, d, K_up);
   ctx->plan_dn = fast_plan(1, d, K_dn);
+  ctx->mid_plan_up = mid_plan(rows, d, K_up);
+  ctx->mid_plan_dn = mid_plan(1, d, K_dn);
   bool ok = dev_alloc(ctx, &ctx->dense.hist, (size_t)rows * dense_row_hist_words()) &&
             dev_alloc(ctx, &ctx->dense.state, (size_t)rows) &&
-            dev_alloc(ctx, &ctx->dense.cnt_gt, (size_t)rows * nwc) &&
-            dev_alloc(ctx, &ctx->dense.cnt_eq, (size_t)rows * nwc) &&
-            dev_alloc(ctx, &ctx->dense.tile_sums, (size_t)rows * 2 * dense_scan_tiles(nwc)) &&
+            dev_alloc(ctx, &ctx->dense.cnt, (size_t)rows * nwc) &&
+            dev_alloc(ctx, &ctx->dense.block_sums, (size_t)rows * dense_max_blocks(1)) &&
             dev_alloc(ctx, &ctx->agg_ranges, (size_t)aggregate_scratch_words(d)) &&
             dev_alloc(ctx, &ctx->agg_offsets, (size_t)aggregate_scratch_words(d)) &&
             alloc_agg_tables(ctx);
@@ -251,6 +318,16 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   if (!alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_dn)) {
     (void)hipGetLastError();
     ctx->plan_dn.enabled = false;
+  }
+  ctx->mid_up.dirty = &ctx->mid_up_dirty;
+  ctx->mid_dn.dirty = &ctx->mid_dn_dirty;
+  if (!alloc_mid(ctx, ctx->mid_plan_up, rows, &ctx->mid_up)) {
+    (void)hipGetLastError();
+    ctx->mid_plan_up.enabled = false;
+  }
+  if (!alloc_mid(ctx, ctx->mid_plan_dn, 1, &ctx->mid_dn)) {
+    (void)hipGetLastError();
+    ctx->mid_plan_dn.enabled = false;
   }
   // The scratch was cleared with hipMemset on the null stream; the context's stream may be
   // a non-blocking one that does not order itself after it.
@@ -281,9 +358,7 @@ int sparse_aggregate(bts_ctx* ctx, const uint32_t* up_idx, const float* up_val, 
                      float* delta, uint32_t* union_nnz) {
   if (!ctx || !p || !delta) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
-  hipError_t e = aggregate(ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, delta,
-                           ctx->d, union_nnz, agg_scratch(ctx));
-  return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
+  return aggregate_messages(ctx, up_idx, up_val, p, delta, union_nnz, false);
 }
 
 int downlink_topk(bts_ctx* ctx, float* delta, uint32_t* dn_idx, float* dn_val) {
@@ -305,13 +380,13 @@ int bidir_step(bts_ctx* ctx, const float* g, float* eps, float* delta, float* w,
                float alpha_in, float alpha_out, uint32_t* up_idx, float* up_val,
                uint32_t* dn_idx, float* dn_val, uint32_t* union_nnz) {
   if (!step_args_ok(ctx, g, eps, delta, w, p, up_idx, up_val, dn_idx, dn_val)) return BTS_EINVAL;
-  int rc = topk_compress(ctx, g, eps, alpha_in, up_idx, up_val);
+  bool ranges = true;       // the aggregation follows on exactly these messages
+  int rc = run_select(ctx, true, g, eps, alpha_in, up_idx, up_val, nullptr,
+                      FusedUpdate{nullptr, 0.0f}, &ranges);
   if (rc != BTS_OK) return rc;
-  rc = sparse_aggregate(ctx, up_idx, up_val, p, delta, union_nnz);
+  rc = aggregate_messages(ctx, up_idx, up_val, p, delta, union_nnz, ranges);
   if (rc != BTS_OK) return rc;
-  rc = downlink_topk(ctx, delta, dn_idx, dn_val);
-  if (rc != BTS_OK) return rc;
-  return sparse_sgd_update(ctx, dn_idx, dn_val, ctx->K_dn, alpha_out, w);
+  return downlink_and_update(ctx, delta, dn_idx, dn_val, alpha_out, w);
 }
 
 int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float* p,
@@ -321,11 +396,13 @@ int unidir_step(bts_ctx* ctx, const float* g, float* eps, float* w, const float*
   if (!aligned16(g) || !aligned16(eps)) return BTS_EINVAL;
   if (ctx->K_up > 0 && (!up_idx || !up_val)) return BTS_EINVAL;
   if ((dn_idx == nullptr) != (dn_val == nullptr)) return BTS_EINVAL;
-  int rc = topk_compress(ctx, g, eps, alpha_in, up_idx, up_val);
+  bool ranges = true;
+  int rc = run_select(ctx, true, g, eps, alpha_in, up_idx, up_val, nullptr,
+                      FusedUpdate{nullptr, 0.0f}, &ranges);
   if (rc != BTS_OK) return rc;
   hipError_t e = aggregate_update_unidirectional(
       ctx->stream, up_idx, up_val, p, (uint32_t)ctx->N, ctx->K_up, w, ctx->d, alpha_out, dn_idx,
-      dn_val, dn_count, agg_scratch(ctx));
+      dn_val, dn_count, agg_scratch(ctx), ranges);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
 
@@ -377,9 +454,7 @@ int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, floa
   if (rc != BTS_OK) return rc;
   rc = sparse_aggregate(ctx, up_idx, up_val, p, delta, nullptr);
   if (rc != BTS_OK) return rc;
-  rc = downlink_topk(ctx, delta, dn_idx, dn_val);
-  if (rc != BTS_OK) return rc;
-  rc = sparse_sgd_update(ctx, dn_idx, dn_val, ctx->K_dn, alpha_out, w);
+  rc = downlink_and_update(ctx, delta, dn_idx, dn_val, alpha_out, w);
   if (rc != BTS_OK) return rc;
   RowEnergy re{};
   if (energy) {
@@ -427,7 +502,10 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
   const uint32_t K = which == 0 ? ctx->K_up : ctx->K_dn;
   *rows_fast = 0;
   *rows_dense = rows;
-  if (!use_fast(ctx, pl) || K == 0) return BTS_OK;
+  const MidPlan& mp = which == 0 ? ctx->mid_plan_up : ctx->mid_plan_dn;
+  if (K == 0 || (ctx->path_mode == 0 && row_select_fits(ctx->d)) || use_mid(ctx, mp) ||
+      !use_fast(ctx, pl))
+    return BTS_OK;
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e);
   std::vector<uint32_t> need(rows);
@@ -444,12 +522,13 @@ int bts_testing_mark_dirty(bts_ctx* ctx) {
   if (!ctx) return BTS_EINVAL;
   ctx->dense_dirty = true;
   ctx->fast_up_dirty = ctx->fast_dn_dirty = ctx->fast_diag_u_dirty = true;
+  ctx->mid_up_dirty = ctx->mid_dn_dirty = true;
   ctx->agg_tables_bad = true;
   return BTS_OK;
 }
 
 int bts_set_path(bts_ctx* ctx, int mode) {
-  if (!ctx || mode < 0 || mode > 2) return BTS_EINVAL;
+  if (!ctx || mode < 0 || mode > 3) return BTS_EINVAL;
   ctx->path_mode = mode;
   return BTS_OK;
 }

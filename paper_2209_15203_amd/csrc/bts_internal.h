@@ -23,6 +23,14 @@ struct SelState {
   uint32_t r;        // how many coordinates with key == T are kept (lowest indices first)
 };
 
+// Model update line of Algorithm 2 fused into the emission of a ONE-ROW select (the server's
+// compression): the lane that writes the pair (i, v) of the message also does
+// w[i] = fma(neg_alpha, v, w[i]).  w == nullptr: no update.
+struct FusedUpdate {
+  float* w;
+  float neg_alpha;
+};
+
 // Rows that a gated kernel must process (null pointer = all rows).
 using RowMask = const uint32_t*;
 
@@ -31,12 +39,12 @@ struct DenseScratch {
   bool* dirty;        // host flag: a call failed half way, clear the histograms first
   uint32_t rows;      // rows the scratch was sized for
   SelState* state;    // rows
-  uint32_t* cnt_gt;   // rows x nwc: per wave-chunk count of key > T, then exclusive offsets
-  uint32_t* cnt_eq;   // rows x nwc: same for key == T
-  uint32_t* tile_sums;  // rows x 2 x dense_scan_tiles(nwc)
+  uint2* cnt;         // rows x nwc: per wave chunk, the counts of key > T (x), key == T (y)
+  uint2* block_sums;  // rows x dense_max_blocks(1): the same per block's share of chunks
   uint32_t nwc;       // wave-chunks per row (upper bound, same for every row)
 };
-uint32_t dense_scan_tiles(uint32_t nwc);
+constexpr uint32_t kDenseMaxGx = 512;     // most blocks per row of a dense pass (a lone row)
+uint32_t dense_max_blocks(uint32_t rows);  // most blocks per row when `rows` rows are selected
 uint32_t dense_row_hist_words();
 
 // ---- dense exact select (handles any input, any K in 1..d) ----------------------------
@@ -47,7 +55,7 @@ uint32_t dense_row_hist_words();
 hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
                         float* out_val, RowMask need, bool first_pass_done,
-                        hipEvent_t ev0, hipEvent_t ev1);
+                        hipEvent_t ev0, hipEvent_t ev1, FusedUpdate upd = FusedUpdate{nullptr, 0.0f});
 
 // The pieces of dense_select for a caller that runs the first four kernels (three digit
 // histograms and the per-chunk counts, see dense_bodies.h) inside launches of its own:
@@ -61,7 +69,7 @@ DensePlan dense_plan(const DenseScratch& sc, uint32_t rows, uint64_t d);
 hipError_t dense_begin(hipStream_t s, const DenseScratch& sc);
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
-                        float* out_val, RowMask need);
+                        float* out_val, RowMask need, FusedUpdate upd);
 
 // x = fma(alpha, g, x) over rows x d and nothing else (K == 0).
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
@@ -72,7 +80,7 @@ bool row_select_fits(uint64_t d);
 // Same contract as dense_select without the row mask.
 hipError_t row_select(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
                       uint32_t K, float alpha, uint32_t* out_idx, float* out_val,
-                      hipEvent_t ev0, hipEvent_t ev1);
+                      hipEvent_t ev0, hipEvent_t ev1, FusedUpdate upd = FusedUpdate{nullptr, 0.0f});
 
 // ---- speculative single-pass select (exact; flags rows it cannot finish) -----------------
 struct FastPlan {
@@ -117,9 +125,46 @@ size_t fast_hist_words();
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
-                       const DenseScratch& dense, bool energy);
+                       const DenseScratch& dense, bool energy,
+                       FusedUpdate upd = FusedUpdate{nullptr, 0.0f});
+
+// ---- middling rows, small K: three launches, no fallback (mid_select.hip) ------------------
+struct MidPlan {
+  bool enabled;            // false: the shape is served by the other paths
+  bool preferred;          // the default choice for this shape
+  uint32_t cap;            // capacity of one candidate list (cannot overflow)
+  uint32_t ntiles;         // directory tiles (64 wave chunks) per row
+  uint32_t nwc_pad;        // directory entries per row (ntiles * 64)
+  uint32_t gx;             // blocks per row of the capture pass (256 threads)
+  uint32_t gx_hist;        // blocks per row of the histogram pass (1024 threads)
+};
+struct MidScratch {
+  uint32_t* hist;          // rows x mid_hist_words() (zero between calls)
+  void* bound;             // rows x mid_bound_bytes(): lower bound and keys above it
+  uint32_t* cand_cnt;      // rows x lists, one counter per 128-byte line (zero between calls)
+  uint2* cand;             // rows x lists x cap (index, value bits)
+  uint2* dir;              // rows x nwc_pad (zero between calls)
+  bool* dirty;             // host flag: a call failed half way, clear the scratch first
+  uint32_t rows;           // rows the scratch was sized for
+};
+// The aggregation's range tables, filled for the worker rows by the select's last kernel so
+// that the aggregation needs no pass of its own over the messages (null: not wanted).
+struct MidRanges {
+  uint32_t* tab_start;
+  uint32_t* tab_end;
+  uint32_t* any;
+};
+MidPlan mid_plan(uint32_t rows, uint64_t d, uint32_t K);
+size_t mid_bound_bytes();
+uint32_t mid_hist_words();
+// Same contract as dense_select without the row mask.
+hipError_t mid_select(hipStream_t s, const MidScratch& sc, const MidPlan& pl, const float* g,
+                      float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
+                      uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
+                      FusedUpdate upd, const MidRanges& ranges);
 
 // ---- server side ------------------------------------------------------------------------
+constexpr uint32_t kAggWidth = 1024;   // coordinates per range of the aggregation
 uint32_t aggregate_ranges(uint64_t d);
 uint32_t aggregate_scratch_words(uint64_t d);
 struct AggScratch {
@@ -129,9 +174,11 @@ struct AggScratch {
   uint32_t* tab_end;    //   replace the per-range binary searches; null = search
   uint32_t* any;        // aggregate_ranges(d) flags (all zero between calls), used with the tables
 };
+// ranges_ready: the tables and flags of sc were already filled for these messages (by the
+// select that wrote them).
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
-                     const AggScratch& sc);
+                     const AggScratch& sc, bool ranges_ready = false);
 // Algorithm 1's server and update in one: w -= alpha_out * sum_q p_q Top_K(a^q), the sum
 // also returned as a sparse message (named coordinates ascending; msg_idx/msg_val nullable,
 // room for N*K_up pairs; msg_count nullable).
@@ -139,7 +186,7 @@ hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx
                                            const float* up_val, const float* p, uint32_t N,
                                            uint32_t K_up, float* w, uint64_t d, float alpha_out,
                                            uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
-                                           const AggScratch& sc);
+                                           const AggScratch& sc, bool ranges_ready = false);
 // ---- per-step diagnostics (rho, rho_hat, 1 - gamma, nnz fraction) -------------------------
 struct DiagScratch {
   float* u;          // d: sum_q p_q a^q

@@ -151,17 +151,37 @@ __device__ __forceinline__ void hist_body(const VGrid vg, const float* __restric
   }
 }
 
-// Per wave-chunk: how many coordinates lie strictly above the threshold key, how many
-// on it.
+// The count and the emission cut a row's wave chunks into contiguous shares, one per block
+// of the (virtual) grid: block bx takes chunks [bx * cpb, (bx + 1) * cpb) and its waves go
+// through them side by side (wave w takes the w-th, (w + 4)-th, ... chunk of the share).
+// Where a share starts in the row's message follows from the totals of the shares before
+// it, and where a chunk starts inside the share from the share's own per-chunk counts: no
+// scan over all the chunks, no pass of its own.
+constexpr uint32_t kMaxShare = 1024;       // most chunks of one block's share
+
+struct ChunkShare {
+  uint32_t begin, end;       // the block's chunks
+};
+
+__device__ __forceinline__ ChunkShare block_share(const VGrid vg, uint32_t nwc) {
+  const uint32_t cpb = (nwc + vg.gx - 1) / vg.gx;                  // chunks per block
+  ChunkShare s;
+  s.begin = min(vg.bx * cpb, nwc);
+  s.end = min(s.begin + cpb, nwc);
+  return s;
+}
+
+// Per wave chunk (cnt: rows x nwc pairs) and per block's share (block_sums: rows x gx pairs):
+// how many coordinates lie strictly above the threshold key (x), how many on it (y).
 __device__ __forceinline__ void count_body(const VGrid vg, const float* __restrict__ x,
                                            uint64_t d, uint32_t K,
                                            const uint32_t* __restrict__ hist,
-                                           SelState* __restrict__ st,
-                                           uint32_t* __restrict__ cnt_gt,
-                                           uint32_t* __restrict__ cnt_eq, uint32_t nwc,
+                                           SelState* __restrict__ st, uint2* __restrict__ cnt,
+                                           uint2* __restrict__ block_sums, uint32_t nwc,
                                            RowMask need, bool streaming) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
+  __shared__ uint32_t s_gt[kWavesPerBlock], s_eq[kWavesPerBlock];
   const uint32_t row = vg.by;
   if (!row_needed(need, row)) return;
   const Resolved res = resolve_row<3>(hist + (uint64_t)row * kRowHist, K, lds, s_out);
@@ -170,28 +190,42 @@ __device__ __forceinline__ void count_body(const VGrid vg, const float* __restri
     st[row].T = T;
     st[row].r = res.k_rem;
   }
-  for (uint32_t wc = vg.bx * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
-       wc += vg.gx * kWavesPerBlock) {
-  const ChunkGeom c = wave_chunk(d, row, wc);
-  uint32_t gt = 0, eq = 0;
-  if (c.active) {
-    visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f, streaming,
-                       [&](uint64_t, const float (&v)[4], uint32_t mask) {
+  const ChunkShare sh = block_share(vg, nwc);
+  const uint32_t w = threadIdx.x / kWave;
+  uint32_t all_gt = 0, all_eq = 0;
+  for (uint32_t wc = sh.begin + w; wc < sh.end; wc += kWavesPerBlock) {
+    const ChunkGeom c = wave_chunk(d, row, wc);
+    uint32_t gt = 0, eq = 0;
+    if (c.active) {
+      visit_chunk<false>(nullptr, const_cast<float*>(x), c, 0.0f, streaming,
+                         [&](uint64_t, const float (&v)[4], uint32_t mask) {
 #pragma unroll
-                         for (int j = 0; j < 4; ++j) {
-                           const uint32_t key = key_of(v[j]);
-                           const bool in = mask & (1u << j);
-                           gt += (in && key > T) ? 1u : 0u;
-                           eq += (in && key == T) ? 1u : 0u;
-                         }
-                       });
+                           for (int j = 0; j < 4; ++j) {
+                             const uint32_t key = key_of(v[j]);
+                             const bool in = mask & (1u << j);
+                             gt += (in && key > T) ? 1u : 0u;
+                             eq += (in && key == T) ? 1u : 0u;
+                           }
+                         });
+    }
+    gt = wave_sum(gt);
+    eq = wave_sum(eq);
+    if (lane_id() == 0) cnt[(uint64_t)row * nwc + wc] = make_uint2(gt, eq);
+    all_gt += gt;
+    all_eq += eq;
   }
-  gt = wave_sum(gt);
-  eq = wave_sum(eq);
   if (lane_id() == 0) {
-    cnt_gt[(uint64_t)row * nwc + wc] = gt;
-    cnt_eq[(uint64_t)row * nwc + wc] = eq;
+    s_gt[w] = all_gt;
+    s_eq[w] = all_eq;
   }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t a = 0, b = 0;
+    for (int i = 0; i < kWavesPerBlock; ++i) {
+      a += s_gt[i];
+      b += s_eq[i];
+    }
+    block_sums[(uint64_t)row * vg.gx + vg.bx] = make_uint2(a, b);
   }
 }
 

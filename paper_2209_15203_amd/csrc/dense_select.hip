@@ -1,8 +1,11 @@
 // Dense exact Top_K select: a three-digit (11 + 10 + 10 bit) radix select on the 31-bit
 // magnitude key with LDS histograms (each kernel resolves the digits found so far from the
 // finished histograms at its start), followed by an ordered emission that needs no
-// atomics for placement: per-wave-chunk counts of (key > T) and (key == T), an exclusive
-// scan over the chunks of a row, and in-wave ballot/popcount prefix sums.  Ties at the
+// atomics for placement: the row's chunks are cut into contiguous shares (one per block),
+// a pass counts (key > T) and (key == T) per chunk and per share, and the emission finds
+// where a share starts from the totals of the shares before it and where a chunk starts
+// from a scan of the share's own counts in LDS, then ranks inside the chunk with
+// ballot/popcount prefix sums.  Five launches.  Ties at the
 // threshold go to the lowest indices.  Works for every input and every K in 1..d; it is
 // the reference path of the library and the fallback of the speculative single-pass path.
 //
@@ -29,129 +32,124 @@ __global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ g,
 __global__ __launch_bounds__(kBlock) void k_count(const float* __restrict__ x, uint64_t d,
                                                   uint32_t K, const uint32_t* __restrict__ hist,
                                                   SelState* __restrict__ st,
-                                                  uint32_t* __restrict__ cnt_gt,
-                                                  uint32_t* __restrict__ cnt_eq, uint32_t nwc,
+                                                  uint2* __restrict__ cnt,
+                                                  uint2* __restrict__ block_sums, uint32_t nwc,
                                                   RowMask need, bool streaming) {
-  count_body(VGrid{blockIdx.x, blockIdx.y, gridDim.x}, x, d, K, hist, st, cnt_gt, cnt_eq, nwc,
+  count_body(VGrid{blockIdx.x, blockIdx.y, gridDim.x}, x, d, K, hist, st, cnt, block_sums, nwc,
              need, streaming);
 }
 
-// Exclusive scan of the per-chunk counts of every row, in place, in two levels: sums of
-// tiles of kScanTile chunks, then each tile scanned from the sum of the tiles before it.
-constexpr uint32_t kScanTile = 4096;
-
-__global__ __launch_bounds__(1024) void k_tile_sums(const uint32_t* __restrict__ cnt_gt,
-                                                    const uint32_t* __restrict__ cnt_eq,
-                                                    uint32_t nwc, uint32_t ntiles,
-                                                    uint32_t* __restrict__ tile_sums,
-                                                    RowMask need) {
-  __shared__ uint32_t lds[1024 / kWave + 1];
-  const uint32_t row = blockIdx.y, tile = blockIdx.x;
-  if (!row_needed(need, row)) return;
-  const uint32_t b = tile * kScanTile, e = min(b + kScanTile, nwc);
-#pragma unroll 1
-  for (int which = 0; which < 2; ++which) {
-    const uint32_t* a = (which == 0 ? cnt_gt : cnt_eq) + (uint64_t)row * nwc;
-    uint32_t s = 0;
-    for (uint32_t i = b + threadIdx.x; i < e; i += blockDim.x) s += a[i];
-    uint32_t total;
-    (void)block_exclusive_scan(s, lds, &total);
-    if (threadIdx.x == 0) tile_sums[((uint64_t)row * 2 + which) * ntiles + tile] = total;
-  }
-}
-
-__global__ __launch_bounds__(1024) void k_scan_chunks(uint32_t* __restrict__ cnt_gt,
-                                                      uint32_t* __restrict__ cnt_eq,
-                                                      uint32_t nwc, uint32_t ntiles,
-                                                      const uint32_t* __restrict__ tile_sums,
-                                                      RowMask need) {
-  __shared__ uint32_t lds[1024 / kWave + 1];
-  const uint32_t row = blockIdx.y, tile = blockIdx.x;
-  if (!row_needed(need, row)) return;
-  const uint32_t b = tile * kScanTile, e = min(b + kScanTile, nwc);
-  constexpr uint32_t kPer = kScanTile / 1024;        // consecutive chunks per thread
-#pragma unroll 1
-  for (int which = 0; which < 2; ++which) {
-    uint32_t* a = (which == 0 ? cnt_gt : cnt_eq) + (uint64_t)row * nwc;
-    const uint32_t* ts = tile_sums + ((uint64_t)row * 2 + which) * ntiles;
-    uint32_t before = 0;
-    for (uint32_t t = threadIdx.x; t < tile; t += blockDim.x) before += ts[t];
-    uint32_t base;
-    (void)block_exclusive_scan(before, lds, &base);  // base = sum over the earlier tiles
-    uint32_t v[kPer];
-    uint32_t s = 0;
-    const uint32_t i0 = b + threadIdx.x * kPer;
-#pragma unroll
-    for (uint32_t k = 0; k < kPer; ++k) {
-      v[k] = i0 + k < e ? a[i0 + k] : 0u;
-      s += v[k];
-    }
-    uint32_t total;
-    uint32_t run = base + block_exclusive_scan(s, lds, &total);
-#pragma unroll
-    for (uint32_t k = 0; k < kPer; ++k) {
-      if (i0 + k < e) a[i0 + k] = run;
-      run += v[k];
-    }
-  }
-}
-
-// Ordered emission.  Every wave re-reads its chunk, ranks its kept coordinates with
-// ballots and writes (index, value) to the row's message at
+// Ordered emission.  A block owns the same contiguous share of chunks as in the count.  The
+// kept coordinates before the share number the totals of the shares before it; the counts
+// of the share's own chunks are scanned in LDS.  The waves then re-read the share's chunks
+// side by side, rank their kept coordinates with ballots and write (index, value) to the
+// row's message at
 //     #kept before it = #(key > T) before it + min(#(key == T) before it, r),
-// then stores +0 over the kept coordinate (the residual).
+// then store +0 over the kept coordinate (the residual).
 __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t d, uint32_t K,
                                                  const SelState* __restrict__ st,
-                                                 const uint32_t* __restrict__ off_gt,
-                                                 const uint32_t* __restrict__ off_eq,
+                                                 const uint2* __restrict__ cnt,
+                                                 const uint2* __restrict__ block_sums,
                                                  uint32_t nwc, uint32_t* __restrict__ out_idx,
                                                  float* __restrict__ out_val,
                                                  uint32_t* __restrict__ hist, RowMask need,
-                                                 bool streaming) {
+                                                 bool streaming, FusedUpdate upd) {
+  __shared__ uint32_t lds[kBlock / kWave + 1];
+  __shared__ uint32_t s_gt[kMaxShare], s_eq[kMaxShare];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) return;
   if (blockIdx.x == 0)                             // leave the row's histograms clear
     for (int i = threadIdx.x; i < kRowHist; i += kBlock) hist[(uint64_t)row * kRowHist + i] = 0;
   const uint32_t T = st[row].T, r = st[row].r;
-  for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
-       wc += gridDim.x * kWavesPerBlock) {
-  const ChunkGeom c = wave_chunk(d, row, wc);
-  if (!c.active) break;
-  uint32_t run_gt = off_gt[(uint64_t)row * nwc + wc];   // wave-uniform running counts
-  uint32_t run_eq = off_eq[(uint64_t)row * nwc + wc];
+  const VGrid vg{blockIdx.x, blockIdx.y, gridDim.x};
+  const ChunkShare sh = block_share(vg, nwc);
+  // kept before this share: every thread adds up some of the earlier shares' totals
+  uint32_t a = 0, b = 0;
+  const uint2* bs = block_sums + (uint64_t)row * vg.gx;
+  for (uint32_t i = threadIdx.x; i < vg.bx; i += kBlock) {
+    const uint2 v = bs[i];
+    a += v.x;
+    b += v.y;
+  }
+  uint32_t base_gt, base_eq;
+  (void)block_exclusive_scan(a, lds, &base_gt);
+  (void)block_exclusive_scan(b, lds, &base_eq);
   uint32_t* oi = out_idx + (uint64_t)row * K;
   float* ov = out_val + (uint64_t)row * K;
-  visit_chunk<false>(nullptr, x, c, 0.0f, streaming,
-                     [&](uint64_t e, const float (&v)[4], uint32_t mask) {
-    uint32_t fgt = 0, feq = 0;
+  // the share in segments of at most kMaxShare chunks (one segment unless the row is
+  // longer than 2.7e8 coordinates)
+  for (uint32_t seg = sh.begin; seg < sh.end; seg += kMaxShare) {
+    const uint32_t n = min(kMaxShare, sh.end - seg);
+    // where each chunk of the segment starts: exclusive scan of its counts (a thread owns
+    // kMaxShare / kBlock consecutive chunks)
+    {
+      constexpr uint32_t kPer = kMaxShare / kBlock;
+      const uint2* cr = cnt + (uint64_t)row * nwc + seg;
+      uint2 v[kPer];
+      uint32_t sg = 0, se = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t key = key_of(v[j]);
-      const bool in = mask & (1u << j);
-      fgt |= (in && key > T) ? (1u << j) : 0u;
-      feq |= (in && key == T) ? (1u << j) : 0u;
-    }
-    if (__ballot(fgt | feq) == 0) return;     // nothing near the threshold in this slice
-    uint32_t tot_gt, tot_eq;
-    uint32_t my_gt = run_gt + wave_exclusive_small(__popc(fgt), &tot_gt);
-    uint32_t my_eq = run_eq + wave_exclusive_small(__popc(feq), &tot_eq);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool is_gt = fgt & (1u << j), is_eq = feq & (1u << j);
-      if (is_gt || (is_eq && my_eq < r)) {
-        const uint32_t pos = my_gt + min(my_eq, r);
-        if (pos < K) {
-          oi[pos] = (uint32_t)(e + j - c.lo);
-          ov[pos] = v[j];
-          x[e + j] = 0.0f;
-        }
+      for (uint32_t k = 0; k < kPer; ++k) {
+        const uint32_t i = threadIdx.x * kPer + k;
+        v[k] = i < n ? cr[i] : make_uint2(0u, 0u);
+        sg += v[k].x;
+        se += v[k].y;
       }
-      my_gt += is_gt ? 1u : 0u;
-      my_eq += is_eq ? 1u : 0u;
+      uint32_t tot_g, tot_e;
+      uint32_t og = base_gt + block_exclusive_scan(sg, lds, &tot_g);
+      uint32_t oe = base_eq + block_exclusive_scan(se, lds, &tot_e);
+#pragma unroll
+      for (uint32_t k = 0; k < kPer; ++k) {
+        const uint32_t i = threadIdx.x * kPer + k;
+        if (i < n) {
+          s_gt[i] = og;
+          s_eq[i] = oe;
+        }
+        og += v[k].x;
+        oe += v[k].y;
+      }
+      base_gt += tot_g;
+      base_eq += tot_e;
     }
-    run_gt += tot_gt;
-    run_eq += tot_eq;
-  });
+    __syncthreads();
+    for (uint32_t wc = seg + threadIdx.x / kWave; wc < seg + n; wc += kWavesPerBlock) {
+      const ChunkGeom c = wave_chunk(d, row, wc);
+      if (!c.active) break;
+      uint32_t run_gt = s_gt[wc - seg], run_eq = s_eq[wc - seg];   // wave-uniform
+      visit_chunk<false>(nullptr, x, c, 0.0f, streaming,
+                         [&](uint64_t e, const float (&v)[4], uint32_t mask) {
+        uint32_t fgt = 0, feq = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t key = key_of(v[j]);
+          const bool in = mask & (1u << j);
+          fgt |= (in && key > T) ? (1u << j) : 0u;
+          feq |= (in && key == T) ? (1u << j) : 0u;
+        }
+        if (__ballot(fgt | feq) == 0) return;     // nothing near the threshold in this slice
+        uint32_t tot_gt, tot_eq;
+        uint32_t my_gt = run_gt + wave_exclusive_small(__popc(fgt), &tot_gt);
+        uint32_t my_eq = run_eq + wave_exclusive_small(__popc(feq), &tot_eq);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool is_gt = fgt & (1u << j), is_eq = feq & (1u << j);
+          if (is_gt || (is_eq && my_eq < r)) {
+            const uint32_t pos = my_gt + min(my_eq, r);
+            if (pos < K) {
+              const uint32_t i = (uint32_t)(e + j - c.lo);
+              oi[pos] = i;
+              ov[pos] = v[j];
+              x[e + j] = 0.0f;
+              if (upd.w != nullptr) upd.w[i] = __fmaf_rn(upd.neg_alpha, v[j], upd.w[i]);
+            }
+          }
+          my_gt += is_gt ? 1u : 0u;
+          my_eq += is_eq ? 1u : 0u;
+        }
+        run_gt += tot_gt;
+        run_eq += tot_eq;
+      });
+    }
+    __syncthreads();                              // the next segment reuses the LDS offsets
   }
 }
 
@@ -178,7 +176,10 @@ __global__ void k_fill(uint32_t* p, uint64_t n, uint32_t v) {
 
 }  // namespace
 
-uint32_t dense_scan_tiles(uint32_t nwc) { return (nwc + kScanTile - 1) / kScanTile; }
+uint32_t dense_max_blocks(uint32_t rows) {
+  const uint32_t lim = kDenseMaxGx / (rows ? rows : 1u);
+  return lim < 256u ? 256u : lim;
+}
 
 hipError_t fill_u32(hipStream_t s, uint32_t* p, uint64_t n, uint32_t v) {
   if (n == 0) return hipSuccess;
@@ -210,8 +211,7 @@ DensePlan dense_plan(const DenseScratch& sc, uint32_t rows, uint64_t d) {
   // at least 256 blocks per row, so that a lone row that falls back still streams fast;
   // a single row gets 512 (measured at d = 1.1e7: 512 blocks beat 256 by their streaming,
   // 2048 and 4096 lose 40 and 120 us per select to the flush into the row's histogram)
-  uint32_t lim = 512u / rows;
-  if (lim < 256u) lim = 256u;
+  const uint32_t lim = dense_max_blocks(rows);
   if (gx > lim) gx = lim;
   pl.gx = gx;
   // rows that are read five times stay in the caches when they are small; beyond the 256 MB
@@ -231,20 +231,12 @@ hipError_t dense_begin(hipStream_t s, const DenseScratch& sc) {
 
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
-                        float* out_val, RowMask need) {
+                        float* out_val, RowMask need, FusedUpdate upd) {
+  if (upd.w != nullptr && rows != 1) return hipErrorInvalidValue;
   const uint32_t nwc = pl.nwc;
-  const uint32_t ntiles = (nwc + kScanTile - 1) / kScanTile;
-  if (ntiles > 1) {                                // a single tile starts from zero
-    k_tile_sums<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
-                                                          sc.tile_sums, need);
-    BTS_LAUNCH_CHECK();
-  }
-  k_scan_chunks<<<dim3(ntiles, rows), dim3(1024), 0, s>>>(sc.cnt_gt, sc.cnt_eq, nwc, ntiles,
-                                                          sc.tile_sums, need);
-  BTS_LAUNCH_CHECK();
-  k_emit<<<dim3(pl.gx, rows), dim3(kBlock), 0, s>>>(x, d, K, sc.state, sc.cnt_gt, sc.cnt_eq, nwc,
-                                                    out_idx, out_val, sc.hist, need,
-                                                    pl.streaming);
+  k_emit<<<dim3(pl.gx, rows), dim3(kBlock), 0, s>>>(x, d, K, sc.state, sc.cnt,
+                                                    sc.block_sums, nwc, out_idx, out_val,
+                                                    sc.hist, need, pl.streaming, upd);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   return hipSuccess;
@@ -253,7 +245,7 @@ hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& 
 hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, float alpha, uint32_t* out_idx,
                         float* out_val, RowMask need, bool first_pass_done,
-                        hipEvent_t ev0, hipEvent_t ev1) {
+                        hipEvent_t ev0, hipEvent_t ev1, FusedUpdate upd) {
   const DensePlan pl = dense_plan(sc, rows, d);
   const uint32_t nwc = pl.nwc;
   const bool streaming = pl.streaming;
@@ -275,10 +267,10 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
   BTS_LAUNCH_CHECK();
   k_hist<2, false><<<grid, block, 0, s>>>(nullptr, x, d, 0.0f, K, sc.hist, nwc, need, streaming);
   BTS_LAUNCH_CHECK();
-  k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt_gt, sc.cnt_eq, nwc, need,
+  k_count<<<grid, block, 0, s>>>(x, d, K, sc.hist, sc.state, sc.cnt, sc.block_sums, nwc, need,
                                  streaming);
   BTS_LAUNCH_CHECK();
-  return dense_finish(s, sc, pl, x, rows, d, K, out_idx, out_val, need);
+  return dense_finish(s, sc, pl, x, rows, d, K, out_idx, out_val, need, upd);
 }
 
 }  // namespace bts

@@ -3,7 +3,7 @@
 //
 // It runs the dense multi-pass select of dense_select.hip -- the same kernels topk_compress
 // uses on its dense path -- with the select's scratch (digit histograms, threshold state,
-// per-chunk counts and their scan) laid out in ONE file-scope device array instead of
+// per-chunk and per-block counts of the emission) laid out in ONE file-scope device array instead of
 // buffers owned by a context.  Every GPU the library runs on holds its own copy of that
 // array (kNoallocWords * 4 bytes = 13 MiB) until the process ends.  Nothing here calls
 // hipMalloc, hipFree or an allocating library routine.
@@ -24,7 +24,7 @@ namespace {
 
 constexpr uint32_t kNoallocMaxRows = 256;              // worker rows per call
 constexpr uint64_t kNoallocMaxChunks = 1ull << 20;     // rows x wave chunks per row
-// histograms + threshold state + two per-chunk count arrays + the tile sums of their scan
+// histograms + threshold state + the per-chunk and per-block counts of the emission
 constexpr uint64_t kNoallocWords = 3407872;            // 13 MiB
 
 static __device__ __align__(256) uint32_t scratch[kNoallocWords];
@@ -88,9 +88,9 @@ extern "C" int topk_compress_noalloc(const float* g, float* eps, int32_t N, uint
   // carve the array up (the limits above bound every piece)
   const uint64_t w_hist = round_up_64((uint64_t)rows * dense_row_hist_words());
   const uint64_t w_state = round_up_64((uint64_t)rows * (sizeof(SelState) / 4));
-  const uint64_t w_cnt = round_up_64((uint64_t)rows * nwc);
-  const uint64_t w_tiles = round_up_64((uint64_t)rows * 2 * dense_scan_tiles(nwc));
-  if (w_hist + w_state + 2 * w_cnt + w_tiles > kNoallocWords) return BTS_ELIMIT;
+  const uint64_t w_cnt = round_up_64((uint64_t)rows * nwc * 2);
+  const uint64_t w_blocks = round_up_64((uint64_t)rows * dense_max_blocks(rows) * 2);
+  if (w_hist + w_state + w_cnt + w_blocks > kNoallocWords) return BTS_ELIMIT;
   DenseScratch sc{};
   // The array keeps what the last call left (another shape's counts, the histograms of a
   // call that failed half way): `dirty` makes the select clear the histograms, with a fill
@@ -101,11 +101,9 @@ extern "C" int topk_compress_noalloc(const float* g, float* eps, int32_t N, uint
   at += w_hist;
   sc.state = reinterpret_cast<SelState*>(at);
   at += w_state;
-  sc.cnt_gt = at;
+  sc.cnt = reinterpret_cast<uint2*>(at);
   at += w_cnt;
-  sc.cnt_eq = at;
-  at += w_cnt;
-  sc.tile_sums = at;
+  sc.block_sums = reinterpret_cast<uint2*>(at);
   sc.dirty = &dirty;
   sc.rows = rows;
   sc.nwc = nwc;

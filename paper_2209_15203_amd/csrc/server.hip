@@ -20,7 +20,6 @@ namespace {
 
 constexpr int kAggBlock = 256;
 constexpr int kAggWaves = kAggBlock / kWave;
-constexpr uint32_t kAggWidth = 1024;   // coordinates per range
 constexpr uint32_t kAggStage = 256;    // pairs a wave stages in LDS at a time
 constexpr uint32_t kAggMaxBlocks = 2048;
 
@@ -387,7 +386,7 @@ uint32_t aggregate_scratch_words(uint64_t d) {
 
 hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val, const float* p,
                      uint32_t N, uint32_t K_up, float* delta, uint64_t d, uint32_t* union_nnz,
-                     const AggScratch& sc) {
+                     const AggScratch& sc, bool ranges_ready) {
   if (K_up == 0) {
     if (union_nnz != nullptr) return fill_u32(s, union_nnz, 1, 0);
     return hipSuccess;
@@ -395,7 +394,7 @@ hipError_t aggregate(hipStream_t s, const uint32_t* up_idx, const float* up_val,
   const uint32_t ranges = aggregate_ranges(d);
   const uint32_t blocks = agg_blocks(ranges);
   uint32_t* any = sc.tab_start != nullptr ? sc.any : nullptr;
-  if (sc.tab_start != nullptr) {
+  if (sc.tab_start != nullptr && !ranges_ready) {
     k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(
         up_idx, N, K_up, d, sc.tab_start, sc.tab_end, sc.any);
     hipError_t e0 = hipGetLastError();
@@ -414,7 +413,7 @@ hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx
                                            const float* up_val, const float* p, uint32_t N,
                                            uint32_t K_up, float* w, uint64_t d, float alpha_out,
                                            uint32_t* msg_idx, float* msg_val, uint32_t* msg_count,
-                                           const AggScratch& sc) {
+                                           const AggScratch& sc, bool ranges_ready) {
   if (K_up == 0) {
     if (msg_count != nullptr) return fill_u32(s, msg_count, 1, 0);
     return hipSuccess;
@@ -422,7 +421,7 @@ hipError_t aggregate_update_unidirectional(hipStream_t s, const uint32_t* up_idx
   const uint32_t ranges = aggregate_ranges(d);
   const uint32_t blocks = agg_blocks(ranges);
   uint32_t* any = sc.tab_start != nullptr ? sc.any : nullptr;
-  if (sc.tab_start != nullptr) {
+  if (sc.tab_start != nullptr && !ranges_ready) {
     k_range_bounds<<<dim3((K_up + 255) / 256, N), dim3(256), 0, s>>>(
         up_idx, N, K_up, d, sc.tab_start, sc.tab_end, sc.any);
     hipError_t e0 = hipGetLastError();

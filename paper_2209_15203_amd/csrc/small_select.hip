@@ -38,7 +38,7 @@ __device__ __forceinline__ uint32_t opaque(uint32_t v) {
 template <int E, bool FMA>
 __global__ __launch_bounds__(kRowBlock) void k_row_select(
     const float* __restrict__ g, float* __restrict__ x, uint32_t d, uint32_t K, float alpha,
-    uint32_t* __restrict__ out_idx, float* __restrict__ out_val) {
+    uint32_t* __restrict__ out_idx, float* __restrict__ out_val, FusedUpdate upd) {
   // histogram of the current digit; the first digit (exponent and three mantissa bits: a
   // handful of busy bins) is spread over kCopies copies by lane, or the whole row would
   // serialise on a few LDS words of this one compute unit
@@ -167,6 +167,7 @@ __global__ __launch_bounds__(kRowBlock) void k_row_select(
         oi[pos] = i;
         ov[pos] = v[k];
         xr[i] = 0.0f;
+        if (upd.w != nullptr) upd.w[i] = __fmaf_rn(upd.neg_alpha, v[k], upd.w[i]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -180,18 +181,20 @@ bool row_select_fits(uint64_t d) { return d <= (uint64_t)kRowSlices * kRowBlock;
 // Same contract as dense_select without the row mask; d must satisfy row_select_fits.
 hipError_t row_select(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
                       uint32_t K, float alpha, uint32_t* out_idx, float* out_val,
-                      hipEvent_t ev0, hipEvent_t ev1) {
+                      hipEvent_t ev0, hipEvent_t ev1, FusedUpdate upd) {
   if (!row_select_fits(d)) return hipErrorInvalidValue;
+  if (upd.w != nullptr && rows != 1) return hipErrorInvalidValue;
   const dim3 grid(rows), block(kRowBlock);
   const uint32_t d32 = (uint32_t)d;
   if (ev0) (void)hipEventRecord(ev0, s);
 #define BTS_ROW(E)                                                                        \
   do {                                                                                    \
     if (g != nullptr)                                                                     \
-      k_row_select<E, true><<<grid, block, 0, s>>>(g, x, d32, K, alpha, out_idx, out_val);  \
+      k_row_select<E, true><<<grid, block, 0, s>>>(g, x, d32, K, alpha, out_idx, out_val,   \
+                                                   upd);                                  \
     else                                                                                  \
       k_row_select<E, false><<<grid, block, 0, s>>>(nullptr, x, d32, K, 0.0f, out_idx,      \
-                                                    out_val);                             \
+                                                    out_val, upd);                        \
   } while (0)
   BTS_ROW(kRowSlices);
 #undef BTS_ROW

@@ -32,7 +32,10 @@ SHAPES = [
     # the one-workgroup-per-row path ends at d = 8192
     (64, 8192, 82), (3, 8191, 8191), (2, 7000, 1), (2, 8193, 9),
 ]
-AUTO, DENSE, SINGLE_PASS = 0, 1, 2      # AUTO: by shape (one workgroup per row up to d = 8192)
+# AUTO: by shape (one workgroup per row up to d = 8192; the three-launch select for small K on
+# rows up to 2^22 where the call is bound by launches); THREE_LAUNCH: that select wherever
+# the shape allows it (K <= 8192, K <= d / 64, 8192 < d <= 2^22), else the dense path
+AUTO, DENSE, SINGLE_PASS, THREE_LAUNCH = 0, 1, 2, 3
 
 
 def make_rows(rng, kind, N, d):
@@ -54,11 +57,14 @@ def make_rows(rng, kind, N, d):
 
 @pytest.mark.parametrize("N,d,K", SHAPES)
 @pytest.mark.parametrize("kind", ["normal", "ties", "quantized", "mixed"])
-@pytest.mark.parametrize("path", [AUTO, DENSE, SINGLE_PASS])
+@pytest.mark.parametrize("path", [AUTO, DENSE, SINGLE_PASS, THREE_LAUNCH])
 def test_topk_compress(G, oracle, N, d, K, kind, path):
     import paper_2209_15203_amd as bts
-    if path == AUTO and d > 8192:
-        pytest.skip("by shape this is the dense or the single-pass path, both covered")
+    three_launch_ok = K <= 8192 and K * 64 <= d and 8192 < d <= (1 << 22)
+    if path == AUTO and d > 8192 and not three_launch_ok:
+        pytest.skip("by shape this is the dense path, covered")
+    if path == THREE_LAUNCH and not three_launch_ok:
+        pytest.skip("the shape does not allow the three-launch select (it is the dense path)")
     rng = np.random.default_rng(N * 1000003 + d * 7 + K)
     g, eps0, alpha = make_rows(rng, kind, N, d)
     D = G.dev()
@@ -201,7 +207,8 @@ def test_threshold_far_above_the_sampled_bound_goes_to_the_dense_path(G, oracle)
     G.assert_same_bits(te, h, "eps, second batch")
 
 
-@pytest.mark.parametrize("d,path", [(9001, DENSE), (200_001, DENSE), (200_001, SINGLE_PASS)])
+@pytest.mark.parametrize("d,path", [(9001, DENSE), (200_001, DENSE), (200_001, SINGLE_PASS),
+                                    (200_001, THREE_LAUNCH)])
 def test_special_values_are_ordered_by_magnitude_bits(G, oracle, d, path):
     """NaN > Inf > finite > denormal > zero, +0 ties with -0, values copied bit for bit."""
     import paper_2209_15203_amd as bts
@@ -339,7 +346,7 @@ SMALL = {"C1": 70_001, "C2": 120_002, "C3": 90_008, "C4": 70_003, "C5": 150_000}
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 @pytest.mark.parametrize("mode", ["paper", "literal"])
-@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS])
+@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS, THREE_LAUNCH])
 def test_bidir_step_scaled_configs(G, oracle, name, mode, path):
     """Each benchmark recipe at a d the oracle finishes in seconds (several chunks and a
     ragged tail), a few steps with carried residuals, in the paper's form
@@ -361,7 +368,7 @@ def test_bidir_step_scaled_configs(G, oracle, name, mode, path):
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
-@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS])
+@pytest.mark.parametrize("path", [DENSE, SINGLE_PASS, THREE_LAUNCH])
 def test_unidir_step_scaled_configs(G, oracle, name, path):
     """Algorithm 1 (the paper's unidirectional baseline) as its own entry point: worker
     compression, then w -= alpha_out * sum_q p_q Top_K(a^q) with the sum returned as a
@@ -481,7 +488,7 @@ def test_resume_from_copied_state_and_path_switching(G, oracle):
     gs = [src.step(t) for t in range(1, 5)]
     a = _fresh_state(cfg, D)
     ctx = bts.BtsContext(cfg.N, cfg.d, cfg.K_up, cfg.K_dn)
-    for t, mode in enumerate((SINGLE_PASS, DENSE, SINGLE_PASS, 0)):
+    for t, mode in enumerate((SINGLE_PASS, THREE_LAUNCH, DENSE, 0)):
         ctx.set_path(mode)
         _step(bts, ctx, a, gs[t], p, cfg.alpha)
     b = _fresh_state(cfg, D)

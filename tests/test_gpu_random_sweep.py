@@ -58,6 +58,8 @@ def test_random_case(oracle, seed):
     K_up, K_dn = draw_k(), draw_k()
     kind = KINDS[seed % len(KINDS)]
     path = int(rng.integers(0, 3))
+    if seed % 5 == 4:
+        path = 3                                 # the three-launch select where the shape allows
     alpha = float(rng.choice([1.0, 0.5, 0.01, 0.37]))
     a_out = float(rng.choice([1.0, 0.3]))
     p = rng.dirichlet(np.ones(N)).astype(np.float32)

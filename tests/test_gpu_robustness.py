@@ -23,7 +23,7 @@ def assert_same_bits_nan_payload_masked(got, want, what):
     return int(w_nan.sum())
 
 
-@pytest.mark.parametrize("path", [0, 1, 2])
+@pytest.mark.parametrize("path", [0, 1, 2, 3])
 def test_nan_through_the_multiply_adds(oracle, path):
     """NaN enters through g (quiet, negative, signalling payloads) and is made by
     inf - inf in the error compensation.  Guaranteed: a NaN of a ranks above every other
@@ -67,7 +67,7 @@ def test_nan_through_the_multiply_adds(oracle, path):
     assert int(st.nnz.item()) == want["union_nnz"]
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_step_after_a_failed_call_recovers(oracle, path):
     """The library keeps its scratch clean between calls; after a call that failed half way
     it must clear what that call may have left and stop trusting the aggregation's range
@@ -87,6 +87,8 @@ def test_step_after_a_failed_call_recovers(oracle, path):
         st.step_and_compare(oracle, src.step(t), cfg.alpha, 1.0, f"path {path} step {t}")
     fast, dense = st.ctx.last_path(0)
     assert (fast, dense) == ((cfg.N, 0) if path == 2 else (0, cfg.N))
+    # the three-launch select fills the aggregation's range tables itself; after the forced
+    # failure those tables are no longer trusted and the aggregation searches instead
 
 
 def test_binding_refuses_undersized_tensors():
