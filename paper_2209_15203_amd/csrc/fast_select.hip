@@ -179,8 +179,38 @@ k_stream_capture(const float* __restrict__ g, float* __restrict__ x, uint64_t d,
 // histogram with plain stores: no cross-block atomics, no fences, nothing to clear.
 constexpr int kD1Bits = 12;
 constexpr int kD0Bins = 8192, kD1Bins = 1 << kD1Bits;
-constexpr uint32_t kPartWords = kD0Bins + kD1Bins;    // partial histograms of one block
+constexpr int kD0Coarse = 256;                        // sums over 32 consecutive d0 bins
+constexpr int kD0PerCoarse = kD0Bins / kD0Coarse;
+// partial histograms of one block: d0, d1, then the coarse sums of d0
+constexpr uint32_t kPartWords = kD0Bins + kD1Bins + kD0Coarse;
+constexpr uint32_t kCoarseAt = kD0Bins + kD1Bins;
 constexpr int kCandBlock = 1024;                      // threads per block of the histogram kernels
+constexpr int kListUnroll = 4;                        // list entries per lane in flight
+
+// How the waves of a row's blocks (gridDim.x blocks of 16 waves) divide the row's 64 lists.
+struct ListShare {
+  uint32_t first, list_step;     // the wave's lists: first, first + list_step, ...
+  uint32_t part, parts;          // of each list, every parts-th group of 256 entries from part
+};
+
+__device__ __forceinline__ ListShare list_share() {
+  constexpr uint32_t kWavesPerCandBlock = kCandBlock / kWave;
+  const uint32_t v = blockIdx.x * kWavesPerCandBlock + threadIdx.x / kWave;
+  const uint32_t waves = gridDim.x * kWavesPerCandBlock;
+  ListShare ls;
+  if (waves >= kSubLists) {              // 64 | waves for every grid the host chooses (4, 8 blocks)
+    ls.first = v % kSubLists;
+    ls.list_step = kSubLists;
+    ls.part = v / kSubLists;
+    ls.parts = waves / kSubLists;
+  } else {
+    ls.first = v;
+    ls.list_step = waves;
+    ls.part = 0;
+    ls.parts = 1;
+  }
+  return ls;
+}
 
 __global__ __launch_bounds__(kCandBlock) void k_cand_hist0(const uint2* __restrict__ cand,
                                                        const uint32_t* __restrict__ cand_cnt,
@@ -204,20 +234,83 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist0(const uint2* __restri
   __syncthreads();
   if (s_need) return;
   const uint32_t L = lower_key[row];
-  // a wave per list
-  for (uint32_t sl = blockIdx.x + gridDim.x * (threadIdx.x / kWave); sl < kSubLists;
-       sl += gridDim.x * (kCandBlock / kWave)) {
+  // the row's waves share the lists: wave v of the row takes list v % 64 and, where the row
+  // has more than 64 waves, every (v / 64)-th group of 256 entries of it; four entries per
+  // lane in flight (a list holds thousands of entries where K is a percent of d)
+  const ListShare ls = list_share();
+  for (uint32_t sl = ls.first; sl < kSubLists; sl += ls.list_step) {
     const uint64_t sub = (uint64_t)row * kSubLists + sl;
     const uint32_t cnt = cand_cnt[sub * kCounterStride];
     const uint2* list = cand + sub * cap;
-    for (uint32_t j = lane_id(); j < cnt; j += kWave) {
-      const uint32_t off = (list[j].y & 0x7FFFFFFFu) - L;
-      atomicAdd(&sh[min(off >> kD1Bits, (uint32_t)kD0Bins - 1)], 1u);
+    for (uint32_t j0 = ls.part * kWave * kListUnroll + lane_id(); j0 < cnt;
+         j0 += ls.parts * kWave * kListUnroll) {
+      uint32_t key[kListUnroll];
+#pragma unroll
+      for (int u = 0; u < kListUnroll; ++u) {
+        const uint32_t j = j0 + u * kWave;
+        key[u] = j < cnt ? list[j].y : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < kListUnroll; ++u) {
+        if (j0 + u * kWave >= cnt) break;
+        const uint32_t off = (key[u] & 0x7FFFFFFFu) - L;
+        atomicAdd(&sh[min(off >> kD1Bits, (uint32_t)kD0Bins - 1)], 1u);
+      }
     }
   }
   __syncthreads();
   uint32_t* out = partial + ((uint64_t)row * gridDim.x + blockIdx.x) * kPartWords;
   for (int i = threadIdx.x; i < kD0Bins; i += kCandBlock) out[i] = sh[i];
+  if (threadIdx.x < kD0Coarse) {        // rotated start: no LDS bank conflicts
+    uint32_t c = 0;
+    for (int i = 0; i < kD0PerCoarse; ++i)
+      c += sh[threadIdx.x * kD0PerCoarse + ((i + threadIdx.x) & (kD0PerCoarse - 1))];
+    out[kCoarseAt + threadIdx.x] = c;
+  }
+}
+
+// The d0 bin holding the K-th largest entry from the blocks' partial histograms, coarse sums
+// first (256 x nparts words), then the 32 bins of the coarse bin found (32 x nparts words)
+// instead of all 8192 x nparts.  *above = entries in higher bins.  All threads call this.
+__device__ __forceinline__ uint32_t resolve_d0(const uint32_t* __restrict__ part_row,
+                                               uint32_t nparts, uint32_t K, uint32_t* lds,
+                                               uint32_t* s_out, uint32_t* above) {
+  const int cb = kD0Coarse - 1 - (int)threadIdx.x;        // this thread's coarse bin (if >= 0)
+  uint32_t c = 0;
+  if (cb >= 0)
+    for (uint32_t b = 0; b < nparts; ++b) c += part_row[(uint64_t)b * kPartWords + kCoarseAt + cb];
+  uint32_t total;
+  const uint32_t excl = block_exclusive_scan(c, lds, &total);
+  if (threadIdx.x == 0) {
+    s_out[0] = 0;
+    s_out[1] = 0;
+  }
+  __syncthreads();
+  if (cb >= 0 && excl < K && K <= excl + c) {
+    s_out[0] = (uint32_t)cb;
+    s_out[1] = excl;
+  }
+  __syncthreads();
+  const uint32_t e = s_out[0], above_e = s_out[1];
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    const int fb = kD0PerCoarse - 1 - (int)threadIdx.x;
+    uint32_t f = 0;
+    if (fb >= 0)
+      for (uint32_t b = 0; b < nparts; ++b)
+        f += part_row[(uint64_t)b * kPartWords + e * kD0PerCoarse + fb];
+    const uint32_t incl = wave_inclusive_scan(f);
+    const uint32_t before = above_e + incl - f;
+    if (fb >= 0 && before < K && K <= before + f) {
+      s_out[0] = e * kD0PerCoarse + (uint32_t)fb;
+      s_out[1] = before;
+    }
+  }
+  __syncthreads();
+  const uint32_t bin = s_out[0];
+  *above = s_out[1];
+  __syncthreads();
+  return bin;
 }
 
 __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restrict__ cand,
@@ -234,8 +327,7 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   if (need[row] == 1u) return;             // set by the previous kernel; 2 is set below
   uint32_t* part_row = partial + (uint64_t)row * gridDim.x * kPartWords;
   uint32_t above;
-  const uint32_t b0 =
-      resolve_bins<kD0Bins, kCandBlock>(part_row, gridDim.x, kPartWords, K, lds, s_out, &above);
+  const uint32_t b0 = resolve_d0(part_row, gridDim.x, K, lds, s_out, &above);
   if (b0 == (uint32_t)kD0Bins - 1) {       // T is beyond the window: the dense path redoes the row
     if (blockIdx.x == 0 && threadIdx.x == 0) need[row] = 2u;
     return;
@@ -247,14 +339,25 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) sh[i] = 0;
   __syncthreads();
   const uint32_t L = lower_key[row];
-  for (uint32_t sl = blockIdx.x + gridDim.x * (threadIdx.x / kWave); sl < kSubLists;
-       sl += gridDim.x * (kCandBlock / kWave)) {
+  const ListShare ls = list_share();
+  for (uint32_t sl = ls.first; sl < kSubLists; sl += ls.list_step) {
     const uint64_t sub = (uint64_t)row * kSubLists + sl;
     const uint32_t cnt = cand_cnt[sub * kCounterStride];
     const uint2* list = cand + sub * cap;
-    for (uint32_t j = lane_id(); j < cnt; j += kWave) {
-      const uint32_t off = (list[j].y & 0x7FFFFFFFu) - L;
-      if ((off >> kD1Bits) == b0) atomicAdd(&sh[off & (kD1Bins - 1)], 1u);
+    for (uint32_t j0 = ls.part * kWave * kListUnroll + lane_id(); j0 < cnt;
+         j0 += ls.parts * kWave * kListUnroll) {
+      uint32_t key[kListUnroll];
+#pragma unroll
+      for (int u = 0; u < kListUnroll; ++u) {
+        const uint32_t j = j0 + u * kWave;
+        key[u] = j < cnt ? list[j].y : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < kListUnroll; ++u) {
+        if (j0 + u * kWave >= cnt) break;
+        const uint32_t off = (key[u] & 0x7FFFFFFFu) - L;
+        if ((off >> kD1Bits) == b0) atomicAdd(&sh[off & (kD1Bins - 1)], 1u);
+      }
     }
   }
   __syncthreads();
@@ -647,8 +750,9 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   // 3 + 4. verify and select: a few fat blocks per row, each taking whole lists (about 32768
   // entries of capacity per block)
   uint32_t hb = (uint32_t)(((uint64_t)pl.cap * kSubLists / 2 + 32767) / 32768);
-  if (hb > kMaxHistBlocks) hb = kMaxHistBlocks;
+  if (hb > 4) hb = kMaxHistBlocks;      // 1-4 blocks (16-64 waves) or 8 (two waves per list)
   if (hb < 1) hb = 1;
+  static_assert(kMaxHistBlocks * (kCandBlock / kWave) % kSubLists == 0, "whole waves per list");
   const dim3 hgrid(hb, rows);
   FastSel* sel = reinterpret_cast<FastSel*>(sc.sel);
   k_cand_hist0<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
