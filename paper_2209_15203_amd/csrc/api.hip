@@ -87,6 +87,7 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
   uint64_t* sup = nullptr;
   bool ok = dev_alloc(ctx, &sc->sample_hist, (size_t)rows * 8192) &&
             dev_alloc(ctx, &sc->lower_key, rows) &&
+            dev_alloc(ctx, &sc->upper_key, rows) &&
             dev_alloc(ctx, &sc->cand_cnt, (size_t)rows * fast_sublists() * fast_counter_stride()) &&
             dev_alloc(ctx, &sc->cand, (size_t)rows * fast_sublists() * pl.cap) &&
             dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_words()) &&

@@ -88,6 +88,7 @@ struct FastPlan {
   bool preferred;          // the default choice for this shape
   uint32_t stride;         // every stride-th 256-coordinate slice is sampled
   uint32_t target;         // sampled coordinates wanted at or above the lower bound
+  uint32_t target_u;       // K in sampled coordinates: aims the bound of the early zeroing
   uint32_t cap;            // capacity of one candidate list
   uint32_t stream_waves_per_simd;   // occupancy the dense pass is held to (3, 5 or 6)
   uint32_t ntiles;         // directory tiles (64 wave chunks) per row
@@ -97,6 +98,7 @@ struct FastPlan {
 struct FastScratch {
   uint32_t* sample_hist;   // rows x 8192 (zero between calls)
   uint32_t* lower_key;     // rows
+  uint32_t* upper_key;     // rows: from which key on the dense pass stores +0 (see capture_chunk)
   uint32_t* cand_cnt;      // rows x lists, one counter per 128-byte line
   uint2* cand;             // rows x lists x cap (index, value bits)
   uint32_t* hist;          // rows x fast_hist_words() partial histograms

@@ -29,10 +29,11 @@ static_assert(kUnroll == 1 || kUnroll % 2 == 0, "slices are counted in pairs");
 // flags: bit 4u + j set = element j of the lane's slice u is a hit; v: the lane's values;
 // i0: index in the row of the lane's first element of slice 0 (modulo 2^32 for lanes that
 // start before the row).  All lanes of the wave call this together.
-__device__ __forceinline__ void append_run(uint32_t flags, const float (&v)[kUnroll][4],
+// Returns whether the run did not fit into its list (the row is then redone by the dense path).
+__device__ __forceinline__ bool append_run(uint32_t flags, const float (&v)[kUnroll][4],
                                            uint32_t i0, uint32_t* counter, uint2* list,
                                            uint32_t cap, uint2* dir_entry) {
-  if (__ballot(flags != 0) == 0) return;
+  if (__ballot(flags != 0) == 0) return false;
   // index order: slice 0 of every lane, then slice 1, ...  The hits of two slices are
   // counted in the halves of one word (a slice has 256 elements: no carry) and scanned
   // together.
@@ -71,6 +72,7 @@ __device__ __forceinline__ void append_run(uint32_t flags, const float (&v)[kUnr
       }
     }
   }
+  return base + total > cap;
 }
 
 // ENERGY (diagnostics only): the wave also sums, in fp64, the squares of its chunk's
@@ -83,11 +85,22 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
   return v;
 }
 
+//
+// U (FMA only; 2^31 and above = never): coordinates with key >= U, a bound U >= L near the
+// K-th largest key, are almost surely sent, so +0 instead of a goes to x there with the same
+// 16-byte store that writes the chunk -- otherwise the emission would have to zero them with
+// K scattered 4-byte stores per row, which cost as much time as a tenth of this pass where K
+// is a percent of d.  The value is not lost: it sits in the chunk's run.  Whoever finds out
+// that such a coordinate is not sent after all writes it back from there (the emission: the
+// few entries between U and the threshold; the select: every such entry of a row that it
+// hands to the dense path).  A chunk whose run did not fit into its list has no such copy
+// and writes its values back itself, below.
 template <bool FMA, bool ENERGY>
 __device__ __forceinline__ void capture_chunk(
-    uint32_t row, uint32_t wc, uint32_t L, const float* __restrict__ g, float* __restrict__ x,
-    uint64_t d, float alpha, uint32_t* __restrict__ cand_cnt, uint2* __restrict__ cand,
-    uint32_t cap, uint2* __restrict__ dir, uint32_t nwc_pad, double* __restrict__ energy) {
+    uint32_t row, uint32_t wc, uint32_t L, uint32_t U, const float* __restrict__ g,
+    float* __restrict__ x, uint64_t d, float alpha, uint32_t* __restrict__ cand_cnt,
+    uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir, uint32_t nwc_pad,
+    double* __restrict__ energy) {
   const ChunkGeom c = wave_chunk(d, row, wc);
   if (!c.active) return;
   const uint64_t sub = (uint64_t)row * kSubLists + wc % kSubLists;
@@ -117,7 +130,6 @@ __device__ __forceinline__ void capture_chunk(
         xv[u].y = __fmaf_rn(alpha, gv[u].y, xv[u].y);
         xv[u].z = __fmaf_rn(alpha, gv[u].z, xv[u].z);
         xv[u].w = __fmaf_rn(alpha, gv[u].w, xv[u].w);
-        __builtin_nontemporal_store(xv[u], reinterpret_cast<f4*>(x + e));
       }
       v[u][0] = xv[u].x;
       v[u][1] = xv[u].y;
@@ -125,14 +137,24 @@ __device__ __forceinline__ void capture_chunk(
       v[u][3] = xv[u].w;
 #pragma unroll
       for (int j = 0; j < 4; ++j) flags |= (key_of(v[u][j]) >= L ? 1u : 0u) << (4 * u + j);
+      if (FMA) {
+        f4 st;
+        st.x = key_of(v[u][0]) >= U ? 0.0f : v[u][0];
+        st.y = key_of(v[u][1]) >= U ? 0.0f : v[u][1];
+        st.z = key_of(v[u][2]) >= U ? 0.0f : v[u][2];
+        st.w = key_of(v[u][3]) >= U ? 0.0f : v[u][3];
+        __builtin_nontemporal_store(st, reinterpret_cast<f4*>(x + e));
+      }
     }
   } else {
     int u = 0;
-    visit_chunk<FMA>(g, x, c, alpha, false, [&](uint64_t, const float (&vv)[4], uint32_t mask) {
+    visit_chunk<FMA>(g, x, c, alpha, false, [&](uint64_t e, const float (&vv)[4], uint32_t mask) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         v[u][j] = vv[j];
-        flags |= (((mask >> j) & 1u) && key_of(vv[j]) >= L ? 1u : 0u) << (4 * u + j);
+        const bool mine = ((mask >> j) & 1u) != 0;
+        flags |= (mine && key_of(vv[j]) >= L ? 1u : 0u) << (4 * u + j);
+        if (FMA && mine && key_of(vv[j]) >= U) x[e + j] = 0.0f;    // after the lane's own store of a
       }
       in_row |= mask << (4 * u);
       ++u;
@@ -148,7 +170,18 @@ __device__ __forceinline__ void capture_chunk(
     e = wave_sum_f64(e);
     if (lane_id() == 0) energy[(uint64_t)row * nwc_pad + wc] = e;
   }
-  append_run(flags, v, i0, counter, list, cap, dir_entry);
+  const bool lost = append_run(flags, v, i0, counter, list, cap, dir_entry);
+  if (FMA && lost) {
+    // the run did not fit (the bound was far too low for this row): a goes back to x, after
+    // the stores above (same lane, same address; the wait makes the order explicit)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if ((flags & (1u << (4 * u + j))) && key_of(v[u][j]) >= U)
+          x[e0 + (uint64_t)u * (kWave * 4) + j] = v[u][j];
+  }
 }
 
 // Result of the exact select over the candidate lists of a row.

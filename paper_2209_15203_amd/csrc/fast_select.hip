@@ -110,19 +110,31 @@ __global__ __launch_bounds__(kBlock) void k_sample_hist(
 // Choose the lower bound: the highest bin edge with at least `target` sampled coordinates
 // at or above it (bin 0, i.e. "everything", if the sample is smaller than that).  Clears
 // the sample histogram and the row's append counters.
+//
+// target_u != 0: also choose the bound U from which the dense pass stores +0 instead of a
+// (see capture_chunk): the bin edge whose count of sampled coordinates at or above it comes
+// closest to target_u = K / stride, i.e. closest to K coordinates of the row.  Every
+// coordinate between U and the threshold, on either side, costs one scattered store later,
+// so the closest edge is the cheapest; no choice of U can make the result wrong.
+constexpr uint32_t kNeverKey = 0xFFFFFFFFu;           // above every 31-bit key
+
 __global__ __launch_bounds__(kBlock) void k_pick_bound(uint32_t* __restrict__ shist,
-                                                       uint32_t target,
+                                                       uint32_t target, uint32_t target_u,
                                                        uint32_t* __restrict__ lower_key,
+                                                       uint32_t* __restrict__ upper_key,
                                                        uint32_t* __restrict__ cand_cnt) {
   constexpr int BPT = kSampleBins / kBlock;   // 32
   __shared__ uint32_t lds[kBlock / kWave + 1];
-  __shared__ uint32_t s_bin;
+  __shared__ uint32_t s_bin, s_ubin;
   const uint32_t row = blockIdx.x;
   uint32_t* h = shist + (uint64_t)row * kSampleBins;
   const int top = kSampleBins - 1 - (int)threadIdx.x * BPT;
   uint32_t s = 0;
   for (int i = 0; i < BPT; ++i) s += h[top - i];
-  if (threadIdx.x == 0) s_bin = 0;
+  if (threadIdx.x == 0) {
+    s_bin = 0;
+    s_ubin = kSampleBins;                     // no bound found: nothing is zeroed early
+  }
   uint32_t total;
   const uint32_t excl = block_exclusive_scan(s, lds, &total);
   if (excl < target && target <= excl + s) {
@@ -137,9 +149,27 @@ __global__ __launch_bounds__(kBlock) void k_pick_bound(uint32_t* __restrict__ sh
     }
     s_bin = (uint32_t)bin;
   }
+  if (target_u != 0 && excl < target_u && target_u <= excl + s) {
+    uint32_t acc = excl;
+    for (int i = 0; i < BPT; ++i) {
+      const uint32_t c = h[top - i];
+      if (acc + c >= target_u) {
+        // at or above bin top - i: acc + c samples; above it: acc
+        const bool upper_edge = target_u - acc < acc + c - target_u;
+        s_ubin = (uint32_t)(top - i) + (upper_edge ? 1u : 0u);
+        break;
+      }
+      acc += c;
+    }
+  }
   __syncthreads();
   for (int i = 0; i < BPT; ++i) h[top - i] = 0;
-  if (threadIdx.x == 0) lower_key[row] = s_bin << kSampleShift;
+  if (threadIdx.x == 0) {
+    lower_key[row] = s_bin << kSampleShift;
+    // never below the lower bound (the two targets can land in one bin)
+    const uint32_t ub = s_ubin < s_bin ? s_bin : s_ubin;
+    upper_key[row] = ub >= (uint32_t)kSampleBins ? kNeverKey : ub << kSampleShift;
+  }
   if (threadIdx.x < kSubLists)
     cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride] = 0;
 }
@@ -154,12 +184,13 @@ constexpr int kMaxWavesPerSimd = 8;
 template <bool FMA, bool ENERGY, int WPS>
 __global__ __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_eu(1, WPS))) void
 k_stream_capture(const float* __restrict__ g, float* __restrict__ x, uint64_t d, float alpha,
-                 const uint32_t* __restrict__ lower_key, uint32_t* __restrict__ cand_cnt,
-                 uint2* __restrict__ cand, uint32_t cap, uint2* __restrict__ dir,
-                 uint32_t nwc_pad, double* __restrict__ energy) {
+                 const uint32_t* __restrict__ lower_key, const uint32_t* __restrict__ upper_key,
+                 uint32_t* __restrict__ cand_cnt, uint2* __restrict__ cand, uint32_t cap,
+                 uint2* __restrict__ dir, uint32_t nwc_pad, double* __restrict__ energy) {
   const uint32_t row = blockIdx.y;
   capture_chunk<FMA, ENERGY>(row, blockIdx.x * kStreamWaves + threadIdx.x / kWave, lower_key[row],
-                             g, x, d, alpha, cand_cnt, cand, cap, dir, nwc_pad, energy);
+                             FMA ? upper_key[row] : kNeverKey, g, x, d, alpha, cand_cnt, cand,
+                             cap, dir, nwc_pad, energy);
 }
 
 // ---- 3 + 4. verify and select on the candidate lists -------------------------------------
@@ -313,23 +344,56 @@ __device__ __forceinline__ uint32_t resolve_d0(const uint32_t* __restrict__ part
   return bin;
 }
 
+// A row that goes to the dense path gets back the values the dense pass replaced by +0 (the
+// listed entries with key >= U; a run that did not fit was written back by its own wave).
+// The row's blocks walk its lists with the shares of the histogram passes.
+__device__ __forceinline__ void restore_early_zeros(uint32_t row, const uint2* __restrict__ cand,
+                                                    const uint32_t* __restrict__ cand_cnt,
+                                                    uint32_t cap, uint32_t U,
+                                                    float* __restrict__ x, uint64_t d) {
+  if (U == kNeverKey) return;
+  float* xr = x + (uint64_t)row * d;
+  const ListShare ls = list_share();
+  for (uint32_t sl = ls.first; sl < kSubLists; sl += ls.list_step) {
+    const uint64_t sub = (uint64_t)row * kSubLists + sl;
+    const uint32_t cnt = min(cand_cnt[sub * kCounterStride], cap);
+    const uint2* list = cand + sub * cap;
+    for (uint32_t j0 = ls.part * kWave * kListUnroll + lane_id(); j0 < cnt;
+         j0 += ls.parts * kWave * kListUnroll) {
+#pragma unroll
+      for (int u = 0; u < kListUnroll; ++u) {
+        const uint32_t j = j0 + u * kWave;
+        if (j >= cnt) break;
+        const uint2 en = list[j];
+        if ((en.y & 0x7FFFFFFFu) >= U && en.x < d) xr[en.x] = __uint_as_float(en.y);
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restrict__ cand,
                                                        const uint32_t* __restrict__ cand_cnt,
                                                        uint32_t cap, uint32_t K,
                                                        const uint32_t* __restrict__ lower_key,
+                                                       const uint32_t* __restrict__ upper_key,
                                                        uint32_t* __restrict__ partial,
                                                        FastSel* __restrict__ sel,
-                                                       uint32_t* __restrict__ need) {
+                                                       uint32_t* __restrict__ need,
+                                                       float* __restrict__ x, uint64_t d) {
   __shared__ uint32_t sh[kD1Bins];
   __shared__ uint32_t lds[kCandBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
   const uint32_t row = blockIdx.y;
-  if (need[row] == 1u) return;             // set by the previous kernel; 2 is set below
+  if (need[row] == 1u) {                   // set by the previous kernel; 2 is set below
+    restore_early_zeros(row, cand, cand_cnt, cap, upper_key[row], x, d);
+    return;
+  }
   uint32_t* part_row = partial + (uint64_t)row * gridDim.x * kPartWords;
   uint32_t above;
   const uint32_t b0 = resolve_d0(part_row, gridDim.x, K, lds, s_out, &above);
   if (b0 == (uint32_t)kD0Bins - 1) {       // T is beyond the window: the dense path redoes the row
     if (blockIdx.x == 0 && threadIdx.x == 0) need[row] = 2u;
+    restore_early_zeros(row, cand, cand_cnt, cap, upper_key[row], x, d);
     return;
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -484,9 +548,9 @@ template <int TPW>
 __device__ __forceinline__ void dir_emit_body(
     uint32_t bx, uint32_t row, uint2* __restrict__ dir, uint32_t nwc_pad,
     const uint2* __restrict__ cand, uint32_t cap, const FastSel* __restrict__ sel,
-    const uint32_t* __restrict__ need, const unsigned long long* __restrict__ tile_cnt,
-    uint32_t ntiles, float* __restrict__ x, uint64_t d, uint32_t K,
-    uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
+    const uint32_t* __restrict__ upper_key, const uint32_t* __restrict__ need,
+    const unsigned long long* __restrict__ tile_cnt, uint32_t ntiles, float* __restrict__ x,
+    uint64_t d, uint32_t K, uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
     double* __restrict__ tile_energy, FusedUpdate upd) {
   __shared__ uint32_t s_off[kWavesPerBlock][kTileChunks], s_start[kWavesPerBlock][kTileChunks];
   const uint32_t w = threadIdx.x / kWave;
@@ -503,6 +567,7 @@ __device__ __forceinline__ void dir_emit_body(
   }
   if (need[row]) return;
   const FastSel s = sel[row];
+  const uint32_t U = upper_key[row];       // the dense pass stored +0 where key >= U
   const uint2* cand_row = cand + (uint64_t)row * kSubLists * cap;
   float* xr = x + (uint64_t)row * d;
   uint32_t* oi = out_idx + (uint64_t)row * K;
@@ -544,10 +609,12 @@ __device__ __forceinline__ void dir_emit_body(
             const float val = __uint_as_float(en[k].y);
             oi[pos] = idx;
             ov[pos] = val;
-            xr[idx] = 0.0f;
+            if (key < U) xr[idx] = 0.0f;
             if (upd.w != nullptr) upd.w[idx] = __fmaf_rn(upd.neg_alpha, val, upd.w[idx]);
           }
         } else if (e < t.total) {
+          // stays behind; if the dense pass took it for sent, its value goes back
+          if (key >= U && en[k].x < d) xr[en[k].x] = __uint_as_float(en[k].y);
           const double val = (double)__uint_as_float(en[k].y);
           left += val * val;
         }
@@ -623,13 +690,13 @@ __global__ __launch_bounds__(kBlock) void k_dirscan_hist2(uint32_t own,
 template <int TPW>
 __global__ __launch_bounds__(kBlock) void k_diremit_count(
     uint32_t own, uint32_t own_gx, uint2* dir, uint32_t nwc_pad, const uint2* cand, uint32_t cap,
-    const FastSel* sel, const uint32_t* need, const unsigned long long* tile_cnt,
-    uint32_t ntiles, uint32_t* out_idx, float* out_val, double* tile_energy, FusedUpdate upd,
-    DensePart dp) {
+    const FastSel* sel, const uint32_t* upper_key, const uint32_t* need,
+    const unsigned long long* tile_cnt, uint32_t ntiles, uint32_t* out_idx, float* out_val,
+    double* tile_energy, FusedUpdate upd, DensePart dp) {
   if (blockIdx.x < own)
     dir_emit_body<TPW>(blockIdx.x % own_gx, blockIdx.x / own_gx, dir, nwc_pad, cand, cap, sel,
-                       need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val, tile_energy,
-                       upd);
+                       upper_key, need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val,
+                       tile_energy, upd);
   else
     count_body(dense_vgrid(blockIdx.x - own, dp), dp.x, dp.d, dp.K, dp.hist, dp.state,
                dp.cnt, dp.block_sums, dp.nwc, need, dp.streaming);
@@ -682,6 +749,8 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.enabled = true;
   p.stride = (uint32_t)stride;
   p.target = (uint32_t)target;
+  p.target_u = (uint32_t)((K + stride / 2) / stride);   // K coordinates of the row, in samples
+  if (p.target_u < 1) p.target_u = 1;
   p.cap = (uint32_t)cap;
   // How many waves per SIMD the dense pass is held to (a kernel variant whose register
   // allocation admits no more): a stream of 2 reads : 1 write runs best well below full
@@ -729,14 +798,17 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
     k_sample_hist<false><<<dim3(sample_blocks, rows), block, 0, s>>>(nullptr, x, d, 0.0f,
                                                                      pl.stride, sc.sample_hist);
   BTS_LAUNCH_CHECK();
-  k_pick_bound<<<dim3(rows), block, 0, s>>>(sc.sample_hist, pl.target, sc.lower_key, sc.cand_cnt);
+  k_pick_bound<<<dim3(rows), block, 0, s>>>(sc.sample_hist, pl.target,
+                                            g != nullptr ? pl.target_u : 0u, sc.lower_key,
+                                            sc.upper_key, sc.cand_cnt);
   BTS_LAUNCH_CHECK();
   // 2. the dense pass (a wave of the grid may lie past the row's last chunk, never past
   // the padded directory)
   if (ev0) (void)hipEventRecord(ev0, s);
 #define BTS_CAPTURE(FMA, ENERGY, WPS, G, ALPHA, EN)                                        \
   k_stream_capture<FMA, ENERGY, WPS><<<dense_grid, dim3(kStreamBlock), 0, s>>>(            \
-      G, x, d, ALPHA, sc.lower_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir, pl.nwc_pad, EN)
+      G, x, d, ALPHA, sc.lower_key, sc.upper_key, sc.cand_cnt, sc.cand, pl.cap, sc.dir,      \
+      pl.nwc_pad, EN)
   if (g == nullptr) {
     BTS_CAPTURE(false, false, kMaxWavesPerSimd, nullptr, 0.0f, nullptr);
   } else if (energy) {
@@ -763,7 +835,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                                                   sc.hist, sc.need);
   BTS_LAUNCH_CHECK();
   k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
-                                                  sc.hist, sel, sc.need);
+                                                  sc.upper_key, sc.hist, sel, sc.need, x, d);
   BTS_LAUNCH_CHECK();
   // 4 (rest) + 5 + the first four kernels of the gated dense redo, pair by pair
   const DensePlan dpl = dense_plan(dense, rows, d);
@@ -803,14 +875,14 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   BTS_LAUNCH_CHECK();
   if (sparse_tiles)
     k_diremit_count<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
-                                                    pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                                    tile_cnt, pl.ntiles, out_idx, out_val,
-                                                    tile_energy, upd, dp);
+                                                    pl.nwc_pad, sc.cand, pl.cap, sel,
+                                                    sc.upper_key, sc.need, tile_cnt, pl.ntiles,
+                                                    out_idx, out_val, tile_energy, upd, dp);
   else
     k_diremit_count<1><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
-                                                    pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
-                                                    tile_cnt, pl.ntiles, out_idx, out_val,
-                                                    tile_energy, upd, dp);
+                                                    pl.nwc_pad, sc.cand, pl.cap, sel,
+                                                    sc.upper_key, sc.need, tile_cnt, pl.ntiles,
+                                                    out_idx, out_val, tile_energy, upd, dp);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   // the rest of the redo: scan of the per-chunk counts, emission of the flagged rows

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kBlock) void k_mid_capture(
   if (blockIdx.x == 0 && threadIdx.x == 0) bound[row] = MidBound{L, above};
   for (uint32_t wc = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; wc < nwc;
        wc += gridDim.x * kWavesPerBlock)
-    capture_chunk<false, false>(row, wc, L, nullptr, x, d, 0.0f, cand_cnt, cand, cap, dir,
+    capture_chunk<false, false>(row, wc, L, 0xFFFFFFFFu, nullptr, x, d, 0.0f, cand_cnt, cand, cap, dir,
                                 nwc_pad, nullptr);
 }
 
