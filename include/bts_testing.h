@@ -34,7 +34,7 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
  * by shape (one workgroup per row up to d = 8192; the three-launch select for K <= 3072,
  * K <= d/64 on rows up to 2^22 coordinates and calls of at most 2.4e7 coordinates, which are
  * bound by their launches; otherwise the single-pass select from about 1.1e7 coordinates per
- * call, 2.5e7 for a single row; else the dense multi-pass select); 1: the dense multi-pass
+ * call, 8e6 for a single row; else the dense multi-pass select); 1: the dense multi-pass
  * path only (the path that also serves as the fallback); 2: the single-pass path wherever the
  * shape allows it (d >= 65536 and K <= d/64), whatever its size; 3: the three-launch path
  * wherever the shape allows it (1 <= K <= 8192, K <= d/64, 8192 < d <= 2^22, at most 2^25

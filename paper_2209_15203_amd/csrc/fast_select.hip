@@ -717,9 +717,10 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   if (K == 0 || d < (1ull << 16) || (uint64_t)K * 64 > d) return p;
   // Small calls are bound by kernel launches and the dense path, with fewer launches, is
   // the quicker one.  Measured crossovers: 1.1e7 coordinates per call for several rows (at
-  // 1.2e7 the single pass is 8 % ahead, at 2.4e7 21 %; at 8e6 the dense path is 6 % ahead),
-  // 2.5e7 for a single row, which the dense path spreads over the chip just as well.
-  p.preferred = rows == 1 ? d >= 25000000ull : (uint64_t)rows * d >= 11000000ull;
+  // 1.2e7 the single pass is 8 % ahead, at 2.4e7 21 %; at 8e6 the dense path is 6 % ahead);
+  // 8e6 for a single row (per select at K = d / 1000: level at 5e6, 5 us ahead at 7e6, 39 us
+  // at 2e7; at K = d / 100: 10 us behind at 5e6, 12 us ahead at 1.1e7).
+  p.preferred = rows == 1 ? d >= 8000000ull : (uint64_t)rows * d >= 11000000ull;
   const uint64_t slices = d / 256;
   // Every stride-th slice is sampled: 64 / K of the row, which puts 64 sampled coordinates
   // in the row's top K, or 1 / 171 of the row where that is more (a sample of that size is

@@ -54,6 +54,15 @@ __global__ void k_range_bounds(const uint32_t* __restrict__ up_idx, uint32_t N, 
 }
 
 constexpr uint32_t kAggNoRel = 0xFFFFu;
+constexpr uint32_t kAggRounds = kAggStage / kWave;     // rounds of 64 pairs in a full stage
+constexpr uint32_t kAggNoRange = 0xFFFFFFFFu;
+
+// Where the workers of the first tile enter and leave a range, fetched by the wave while it
+// still works on the range before (one entry per lane).
+struct AggPrefetch {
+  uint32_t lo, hi;
+  bool valid;            // wave-uniform
+};
 
 struct AggWaveLds {
   float acc[kAggWidth];                 // g_t of the touched coordinates
@@ -85,9 +94,15 @@ __device__ __forceinline__ uint32_t seen_byte(const AggWaveLds& L, uint32_t rel)
 // the same coordinate; pairs of one depth name distinct coordinates, so they are applied in
 // parallel, and going through the depths in ascending order applies each coordinate's
 // pairs in ascending q.  Stages and tiles follow each other in ascending q as well.
+//
+// The loads that depend on each other (table entry -> pair -> start value of delta) are what
+// a range costs, so they are issued in batches: the pairs of a stage all at once, the start
+// values of a stage all at once, and the table entries of the wave's next range (r_next)
+// before the work on this one.
 template <int MODE>
 __device__ __forceinline__ uint32_t aggregate_range(
-    AggWaveLds& L, uint32_t r, const uint32_t* __restrict__ up_idx,
+    AggWaveLds& L, uint32_t r, uint32_t r_next, AggPrefetch& pf,
+    const uint32_t* __restrict__ up_idx,
     const float* __restrict__ up_val, const float* __restrict__ p, uint32_t N, uint32_t K_up,
     float* __restrict__ dense, uint64_t d, uint32_t* __restrict__ tab_start,
     uint32_t* __restrict__ tab_end, const uint32_t* __restrict__ range_off, float neg_alpha,
@@ -105,8 +120,9 @@ __device__ __forceinline__ uint32_t aggregate_range(
     if (lane < nq) {
       if (tab_start != nullptr) {
         const uint64_t at = (uint64_t)r * N + q0 + lane;
-        lo = tab_start[at];
-        const uint32_t hi = tab_end[at];
+        const bool ready = q0 == 0 && pf.valid;
+        lo = ready ? pf.lo : tab_start[at];
+        const uint32_t hi = ready ? pf.hi : tab_end[at];
         n = (hi > lo && hi <= K_up) ? hi - lo : 0u;
         if (MODE != 1 && hi) {                               // leave the table clear
           tab_start[at] = 0;
@@ -119,6 +135,14 @@ __device__ __forceinline__ uint32_t aggregate_range(
       }
       L.p[lane] = p[q0 + lane];
     }
+    if (q0 == 0) {                                           // the next range's first tile
+      pf.valid = tab_start != nullptr && r_next != kAggNoRange;
+      if (pf.valid && lane < nq) {
+        const uint64_t at = (uint64_t)r_next * N + lane;
+        pf.lo = tab_start[at];
+        pf.hi = tab_end[at];
+      }
+    }
     const uint32_t incl = wave_inclusive_scan(n);
     const uint32_t total = __shfl(incl, kWave - 1, kWave);
     if (total == 0) continue;
@@ -128,25 +152,52 @@ __device__ __forceinline__ uint32_t aggregate_range(
     wave_lds_sync();
     for (uint32_t e0 = 0; e0 < total; e0 += kAggStage) {
       const uint32_t ne = min(kAggStage, total - e0);        // pairs in the stage
-      // 1. fetch the stage's pairs (independent loads)
-      for (uint32_t k = lane; k < ne; k += kWave) {
-        const uint32_t e = e0 + k;
-        uint32_t a = 0;                                      // the last worker with pref <= e
+      // 1. fetch the stage's pairs (independent loads, all issued before the first is used)
+      {
+        uint32_t pi[kAggRounds], pa[kAggRounds];
+        float pv[kAggRounds];
 #pragma unroll
-        for (uint32_t st = kWave / 2; st > 0; st >>= 1)
-          if (L.pref[a + st] <= e) a += st;
-        const uint64_t src = (uint64_t)(q0 + a) * K_up + L.lo[a] + (e - L.pref[a]);
-        const uint32_t i = up_idx[src];
-        // inside the range for sorted input
-        const uint32_t rel = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;
-        L.e_key[k] = rel | (a << 16);
-        if (MODE != 1) L.e_val[k] = up_val[src];
+        for (uint32_t it = 0; it < kAggRounds; ++it) {
+          const uint32_t k = it * kWave + lane;
+          pi[it] = 0;
+          pa[it] = 0;
+          pv[it] = 0.0f;
+          if (k < ne) {
+            const uint32_t e = e0 + k;
+            uint32_t a = 0;                                  // the last worker with pref <= e
+#pragma unroll
+            for (uint32_t st = kWave / 2; st > 0; st >>= 1)
+              if (L.pref[a + st] <= e) a += st;
+            const uint64_t src = (uint64_t)(q0 + a) * K_up + L.lo[a] + (e - L.pref[a]);
+            pi[it] = up_idx[src];
+            if (MODE != 1) pv[it] = up_val[src];
+            pa[it] = a;
+          }
+        }
+#pragma unroll
+        for (uint32_t it = 0; it < kAggRounds; ++it) {
+          const uint32_t k = it * kWave + lane;
+          if (k < ne) {
+            const uint32_t i = pi[it];
+            // inside the range for sorted input
+            const uint32_t rel = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;
+            L.e_key[k] = rel | (pa[it] << 16);
+            if (MODE != 1) L.e_val[k] = pv[it];
+          }
+        }
       }
       if (MODE != 1 && lane < kWave) L.lvl_fill[lane] = 0;
       wave_lds_sync();
-      // 2. first touches fetch the start value; depth of every pair
+      // 2. first touches fetch the start value (the loads of all rounds are in flight
+      // together; the values go to the accumulator after the last round); depth of every pair
       const uint32_t rounds = (ne + kWave - 1) / kWave;
-      for (uint32_t it = 0; it < rounds; ++it) {
+      float sv[kAggRounds];
+      uint32_t srel[kAggRounds];
+#pragma unroll
+      for (uint32_t it = 0; it < kAggRounds; ++it) {
+        srel[it] = kAggNoRel;
+        sv[it] = 0.0f;
+        if (it >= rounds) continue;                          // wave-uniform
         const uint32_t k = it * kWave + lane;
         const uint32_t rel = k < ne ? (L.e_key[k] & 0xFFFFu) : kAggNoRel;
         const bool valid = rel != kAggNoRel;
@@ -155,7 +206,10 @@ __device__ __forceinline__ uint32_t aggregate_range(
           const uint32_t bit = 1u << (rel & 31);
           const uint32_t old = atomicOr(&L.touched[rel >> 5], bit);
           if (!(old & bit)) {                                // first touch: start value
-            if (MODE == 0) L.acc[rel] = dense[c0 + rel];
+            if (MODE == 0) {
+              sv[it] = dense[c0 + rel];
+              srel[it] = rel;
+            }
             if (MODE == 2) L.acc[rel] = 0.0f;
             ++fresh;
           }
@@ -166,13 +220,18 @@ __device__ __forceinline__ uint32_t aggregate_range(
           if (valid) atomicAdd(&L.seen[rel >> 2], 1u << (8 * (rel & 3)));
           wave_lds_sync();
           const uint32_t here = valid ? seen_byte(L, rel) - before : 0u;   // of this round
-          uint64_t shared = __ballot(here > 1);              // lanes that share a coordinate
+          // rank among the lanes of this round on the same coordinate: one turn of the loop
+          // per coordinate that several lanes share (none for uncorrelated workers)
+          uint64_t shared = __ballot(here > 1);
           uint32_t rank = 0;
+          const uint64_t below = lanes_below();
           while (shared) {
             const int j = __ffsll((unsigned long long)shared) - 1;
-            shared &= shared - 1;
-            const uint32_t rel_j = __shfl(rel, j, kWave);
-            if (valid && rel == rel_j && (uint32_t)j < lane) ++rank;
+            const uint32_t rel_j = (uint32_t)__builtin_amdgcn_readlane((int)rel, j);
+            const bool same = valid && rel == rel_j;
+            const uint64_t grp = __ballot(same);
+            if (same) rank = (uint32_t)__popcll(grp & below);
+            shared &= ~grp;
           }
           if (valid) {
             // < 64 when no worker names a coordinate twice; clamped for lists that do
@@ -181,6 +240,11 @@ __device__ __forceinline__ uint32_t aggregate_range(
             atomicAdd(&L.lvl_fill[depth], 1u);
           }
         }
+      }
+      if (MODE == 0) {
+#pragma unroll
+        for (uint32_t it = 0; it < kAggRounds; ++it)
+          if (srel[it] != kAggNoRel) L.acc[srel[it]] = sv[it];
       }
       if (MODE != 1) {
         wave_lds_sync();
@@ -270,6 +334,10 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
   const uint32_t W = gridDim.x * kAggWaves;
   for (uint32_t i = lane; i < kAggWidth / 4; i += kWave) L.seen[i] = 0;   // every stage cleans up
   uint32_t nnz = 0;
+  AggPrefetch pf;
+  pf.lo = 0;
+  pf.hi = 0;
+  pf.valid = false;
   for (uint64_t r0 = g; r0 < ranges; r0 += (uint64_t)W * kWave) {
     const uint64_t mine = r0 + (uint64_t)lane * W;
     bool live = mine < ranges;
@@ -283,7 +351,12 @@ __global__ __launch_bounds__(kAggBlock) void k_aggregate(
       const uint32_t src = (uint32_t)__ffsll((unsigned long long)todo) - 1;
       todo &= todo - 1;
       const uint32_t r = (uint32_t)(r0 + (uint64_t)src * W);
-      const uint32_t cnt = aggregate_range<MODE>(L, r, up_idx, up_val, p, N, K_up, dense, d,
+      // the wave's next raised range of this batch of 64, if any
+      const uint32_t r_next =
+          todo ? (uint32_t)(r0 + (uint64_t)((uint32_t)__ffsll((unsigned long long)todo) - 1) * W)
+               : kAggNoRange;
+      const uint32_t cnt = aggregate_range<MODE>(L, r, r_next, pf, up_idx, up_val, p, N, K_up,
+                                                 dense, d,
                                                  tab_start, tab_end, range_off, neg_alpha,
                                                  msg_idx, msg_val);
       if (MODE == 1 && lane == 0) nnz_out[r] = cnt;
