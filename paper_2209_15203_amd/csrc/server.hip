@@ -3,12 +3,13 @@
 // and the model update  w_t = w_{t-1} - Top_K(g_t)  on the received pairs.
 //
 // Aggregation is deterministic without float atomics: the coordinate axis is cut into
-// ranges of kAggWidth coordinates and ONE WAVE owns a range.  It stages the range's pairs
-// in (worker, index) order in its part of LDS, gathers the touched part of delta into an
-// LDS accumulator, and applies the workers one after the other in ascending q (a worker
-// never names a coordinate twice, so the pairs of one worker are applied in parallel).
-// Consecutive workers are ordered by the wave's program order alone: no workgroup barrier
-// and no HBM latency inside the N dependent rounds.  Where each worker's sorted list enters
+// ranges of kAggWidth coordinates and ONE WAVE owns a range.  It takes the range's pairs
+// in (worker, index) order into registers, 256 at a time, gathers the touched part of delta
+// into an LDS accumulator, gives every pair its depth (how many earlier pairs name the same
+// coordinate) and applies the pairs depth by depth: pairs of one depth name distinct
+// coordinates and go in parallel, ascending depths are ascending q for every coordinate.
+// Consecutive depths are ordered by the wave's program order alone: no workgroup barrier
+// and no HBM latency inside the dependent steps.  Where each worker's sorted list enters
 // and leaves each range comes from a table (or from binary searches when the table would be
 // too large), and a flag per range lets a wave skip, 64 at a time, the ranges nobody names.
 
@@ -20,7 +21,7 @@ namespace {
 
 constexpr int kAggBlock = 256;
 constexpr int kAggWaves = kAggBlock / kWave;
-constexpr uint32_t kAggStage = 256;    // pairs a wave stages in LDS at a time
+constexpr uint32_t kAggStage = 256;    // pairs a wave holds in registers at a time (4 per lane)
 constexpr uint32_t kAggMaxBlocks = 2048;
 
 __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__ a, uint32_t n,
@@ -71,11 +72,6 @@ struct AggWaveLds {
   uint32_t lo[kWave];                   // per worker of the tile: first pair in the range
   uint32_t pref[kWave + 1];             // pairs of the tile's earlier workers in the range
   float p[kWave];
-  uint32_t lvl_off[kWave + 1];          // first slot of each depth level in order[]
-  uint32_t lvl_fill[kWave];
-  uint32_t e_key[kAggStage];            // coordinate - c0 (low 16 bits) | worker in the tile << 16
-  float e_val[kAggStage];
-  uint16_t order[kAggStage];            // the stage's pairs grouped by depth level
 };
 
 __device__ __forceinline__ uint32_t seen_byte(const AggWaveLds& L, uint32_t rel) {
@@ -89,8 +85,8 @@ __device__ __forceinline__ uint32_t seen_byte(const AggWaveLds& L, uint32_t rel)
 //         range_off[range] + rank, and w[i] = fma(-alpha_out, g_t[i], w[i]).
 // Returns the number of distinct coordinates named in range r (same value in every lane).
 //
-// The pairs of the range are staged in (worker, index) order, kAggStage at a time (at most
-// 64 workers per tile).  The depth of a pair is the number of earlier pairs of the stage on
+// The pairs of the range are taken in (worker, index) order, kAggStage at a time (at most
+// 64 workers per tile), four per lane, and stay in registers.  The depth of a pair is the number of earlier pairs of the stage on
 // the same coordinate; pairs of one depth name distinct coordinates, so they are applied in
 // parallel, and going through the depths in ascending order applies each coordinate's
 // pairs in ascending q.  Stages and tiles follow each other in ascending q as well.
@@ -152,16 +148,18 @@ __device__ __forceinline__ uint32_t aggregate_range(
     wave_lds_sync();
     for (uint32_t e0 = 0; e0 < total; e0 += kAggStage) {
       const uint32_t ne = min(kAggStage, total - e0);        // pairs in the stage
-      // 1. fetch the stage's pairs (independent loads, all issued before the first is used)
+      // 1. fetch the stage's pairs into registers: lane l holds pairs l, l + 64, ... of the
+      // stage (independent loads, all issued before the first is used)
+      uint32_t rel[kAggRounds];            // coordinate - c0, or kAggNoRel
+      float val[kAggRounds], pw[kAggRounds];
       {
         uint32_t pi[kAggRounds], pa[kAggRounds];
-        float pv[kAggRounds];
 #pragma unroll
         for (uint32_t it = 0; it < kAggRounds; ++it) {
           const uint32_t k = it * kWave + lane;
-          pi[it] = 0;
+          pi[it] = 0xFFFFFFFFu;
           pa[it] = 0;
-          pv[it] = 0.0f;
+          val[it] = 0.0f;
           if (k < ne) {
             const uint32_t e = e0 + k;
             uint32_t a = 0;                                  // the last worker with pref <= e
@@ -170,112 +168,84 @@ __device__ __forceinline__ uint32_t aggregate_range(
               if (L.pref[a + st] <= e) a += st;
             const uint64_t src = (uint64_t)(q0 + a) * K_up + L.lo[a] + (e - L.pref[a]);
             pi[it] = up_idx[src];
-            if (MODE != 1) pv[it] = up_val[src];
+            if (MODE != 1) val[it] = up_val[src];
             pa[it] = a;
           }
         }
 #pragma unroll
         for (uint32_t it = 0; it < kAggRounds; ++it) {
-          const uint32_t k = it * kWave + lane;
-          if (k < ne) {
-            const uint32_t i = pi[it];
-            // inside the range for sorted input
-            const uint32_t rel = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;
-            L.e_key[k] = rel | (pa[it] << 16);
-            if (MODE != 1) L.e_val[k] = pv[it];
-          }
+          const uint32_t i = pi[it];
+          // inside the range for sorted input (never for the slots past the stage's end)
+          rel[it] = (i >= c0 && i < c1) ? i - (uint32_t)c0 : kAggNoRel;
+          pw[it] = MODE != 1 ? L.p[pa[it]] : 0.0f;
         }
       }
-      if (MODE != 1 && lane < kWave) L.lvl_fill[lane] = 0;
-      wave_lds_sync();
       // 2. first touches fetch the start value (the loads of all rounds are in flight
       // together; the values go to the accumulator after the last round); depth of every pair
       const uint32_t rounds = (ne + kWave - 1) / kWave;
       float sv[kAggRounds];
-      uint32_t srel[kAggRounds];
+      bool first[kAggRounds];
+      uint32_t depth[kAggRounds];
+      const uint64_t below = lanes_below();
 #pragma unroll
       for (uint32_t it = 0; it < kAggRounds; ++it) {
-        srel[it] = kAggNoRel;
+        first[it] = false;
         sv[it] = 0.0f;
+        depth[it] = 0;
         if (it >= rounds) continue;                          // wave-uniform
-        const uint32_t k = it * kWave + lane;
-        const uint32_t rel = k < ne ? (L.e_key[k] & 0xFFFFu) : kAggNoRel;
-        const bool valid = rel != kAggNoRel;
+        const uint32_t rl = rel[it];
+        const bool valid = rl != kAggNoRel;
         uint32_t before = 0;
         if (valid) {
-          const uint32_t bit = 1u << (rel & 31);
-          const uint32_t old = atomicOr(&L.touched[rel >> 5], bit);
+          const uint32_t bit = 1u << (rl & 31);
+          const uint32_t old = atomicOr(&L.touched[rl >> 5], bit);
           if (!(old & bit)) {                                // first touch: start value
-            if (MODE == 0) {
-              sv[it] = dense[c0 + rel];
-              srel[it] = rel;
-            }
-            if (MODE == 2) L.acc[rel] = 0.0f;
+            first[it] = true;
+            if (MODE == 0) sv[it] = dense[c0 + rl];
             ++fresh;
           }
-          if (MODE != 1) before = seen_byte(L, rel);
+          if (MODE != 1) before = seen_byte(L, rl);
         }
         if (MODE != 1) {
           wave_lds_sync();
-          if (valid) atomicAdd(&L.seen[rel >> 2], 1u << (8 * (rel & 3)));
+          if (valid) atomicAdd(&L.seen[rl >> 2], 1u << (8 * (rl & 3)));
           wave_lds_sync();
-          const uint32_t here = valid ? seen_byte(L, rel) - before : 0u;   // of this round
+          const uint32_t here = valid ? seen_byte(L, rl) - before : 0u;   // of this round
           // rank among the lanes of this round on the same coordinate: one turn of the loop
           // per coordinate that several lanes share (none for uncorrelated workers)
           uint64_t shared = __ballot(here > 1);
           uint32_t rank = 0;
-          const uint64_t below = lanes_below();
           while (shared) {
             const int j = __ffsll((unsigned long long)shared) - 1;
-            const uint32_t rel_j = (uint32_t)__builtin_amdgcn_readlane((int)rel, j);
-            const bool same = valid && rel == rel_j;
+            const uint32_t rel_j = (uint32_t)__builtin_amdgcn_readlane((int)rl, j);
+            const bool same = valid && rl == rel_j;
             const uint64_t grp = __ballot(same);
             if (same) rank = (uint32_t)__popcll(grp & below);
             shared &= ~grp;
           }
-          if (valid) {
-            // < 64 when no worker names a coordinate twice; clamped for lists that do
-            const uint32_t depth = min(before + rank, (uint32_t)kWave - 1);
-            L.e_key[k] |= depth << 24;                       // worker < 64 fits bits 16..23
-            atomicAdd(&L.lvl_fill[depth], 1u);
-          }
+          // < 64 when no worker names a coordinate twice; clamped for lists that do
+          depth[it] = min(before + rank, (uint32_t)kWave - 1);
         }
-      }
-      if (MODE == 0) {
-#pragma unroll
-        for (uint32_t it = 0; it < kAggRounds; ++it)
-          if (srel[it] != kAggNoRel) L.acc[srel[it]] = sv[it];
       }
       if (MODE != 1) {
-        wave_lds_sync();
-        // 3. group the pairs by depth (the order inside a depth does not matter)
-        const uint32_t cnt = L.lvl_fill[lane];
-        const uint32_t cincl = wave_inclusive_scan(cnt);
-        const uint64_t used = __ballot(cnt != 0);
-        const uint32_t levels = used ? 64u - (uint32_t)__clzll((unsigned long long)used) : 0u;
-        wave_lds_sync();
-        L.lvl_off[lane] = cincl - cnt;
-        L.lvl_fill[lane] = cincl - cnt;
-        if (lane == kWave - 1) L.lvl_off[kWave] = cincl;
-        wave_lds_sync();
-        for (uint32_t k = lane; k < ne; k += kWave) {
-          const uint32_t key = L.e_key[k];
-          if ((key & 0xFFFFu) != kAggNoRel) {
-            L.order[atomicAdd(&L.lvl_fill[key >> 24], 1u)] = (uint16_t)k;
-            L.seen[(key & 0xFFFFu) >> 2] = 0;                // clean for the next stage
-          }
+        // start values in place, the stage's counts cleaned for the next stage
+#pragma unroll
+        for (uint32_t it = 0; it < kAggRounds; ++it) {
+          if (first[it]) L.acc[rel[it]] = sv[it];            // MODE 2: +0
+          if (rel[it] != kAggNoRel) L.seen[rel[it] >> 2] = 0;
         }
         wave_lds_sync();
-        // 4. apply, depth by depth
-        for (uint32_t l = 0; l < levels; ++l) {
-          const uint32_t b = L.lvl_off[l + 1];
-          for (uint32_t j = L.lvl_off[l] + lane; j < b; j += kWave) {
-            const uint32_t k = L.order[j];
-            const uint32_t key = L.e_key[k];
-            const uint32_t rel = key & 0xFFFFu;
-            L.acc[rel] = __fmaf_rn(L.p[(key >> 16) & 0xFFu], L.e_val[k], L.acc[rel]);
+        // 3. apply, depth by depth: pairs of one depth name distinct coordinates
+        for (uint32_t l = 0;; ++l) {
+          bool more = false;
+#pragma unroll
+          for (uint32_t it = 0; it < kAggRounds; ++it) {
+            if (rel[it] == kAggNoRel) continue;
+            if (depth[it] == l) L.acc[rel[it]] = __fmaf_rn(pw[it], val[it], L.acc[rel[it]]);
+            more |= depth[it] > l;
           }
           wave_lds_sync();                                   // the next depth may name the same i
+          if (__ballot(more) == 0) break;
         }
       }
     }
