@@ -21,14 +21,17 @@ struct bts_ctx {
   DenseScratch dense;
   bool dense_dirty;
   bool fast_up_dirty, fast_dn_dirty;
+  uint32_t fast_up_calls, fast_dn_calls, fast_diag_u_calls, fast_diag_v_calls;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
   MidPlan mid_plan_up, mid_plan_dn;   // the three-launch select of middling rows with small K
   MidScratch mid_up, mid_dn;
   bool mid_up_dirty, mid_dn_dirty;
   FastPlan plan_diag_u;         // diagnostics: one row of length d with K_up (the select of
-  FastScratch fast_diag_u;      //   sum_q p_q a^q); the one with K_dn reuses plan_dn / fast_dn
-  bool fast_diag_u_dirty;
+  FastScratch fast_diag_u;      //   sum_q p_q a^q); the one with K_dn follows plan_dn with a
+  FastScratch fast_diag_v;      //   scratch of its own (a scratch hands its bounds from call
+  bool fast_diag_u_dirty;       //   to call, so each sequence of vectors gets one)
+  bool fast_diag_v_dirty;
   uint32_t* agg_ranges;         // per-range distinct-coordinate counts of the aggregation
   uint32_t* agg_offsets;        // their exclusive scan (unidirectional message placement)
   uint32_t *agg_start, *agg_end;  // range x worker entry/exit tables (null: binary search)
@@ -88,6 +91,7 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
   bool ok = dev_alloc(ctx, &sc->sample_hist, (size_t)rows * 8192) &&
             dev_alloc(ctx, &sc->lower_key, rows) &&
             dev_alloc(ctx, &sc->upper_key, rows) &&
+            dev_alloc(ctx, &sc->prev_T, rows) &&
             dev_alloc(ctx, &sc->cand_cnt, (size_t)rows * fast_sublists() * fast_counter_stride()) &&
             dev_alloc(ctx, &sc->cand, (size_t)rows * fast_sublists() * pl.cap) &&
             dev_alloc(ctx, &sc->hist, (size_t)rows * fast_hist_words()) &&
@@ -270,9 +274,13 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->dense = DenseScratch{};
   ctx->dense_dirty = false;
   ctx->fast_up_dirty = ctx->fast_dn_dirty = ctx->fast_diag_u_dirty = false;
+  ctx->fast_diag_v_dirty = false;
+  ctx->fast_up_calls = ctx->fast_dn_calls = ctx->fast_diag_u_calls = 0;
+  ctx->fast_diag_v_calls = 0;
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->fast_diag_u = FastScratch{};
+  ctx->fast_diag_v = FastScratch{};
   ctx->plan_diag_u = FastPlan{};
   ctx->mid_up = MidScratch{};
   ctx->mid_dn = MidScratch{};
@@ -312,6 +320,8 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   // serves the shape alone.
   ctx->fast_up.dirty = &ctx->fast_up_dirty;
   ctx->fast_dn.dirty = &ctx->fast_dn_dirty;
+  ctx->fast_up.calls = &ctx->fast_up_calls;
+  ctx->fast_dn.calls = &ctx->fast_dn_calls;
   if (!alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up)) {
     (void)hipGetLastError();
     ctx->plan_up.enabled = false;
@@ -423,10 +433,14 @@ int bts_enable_diagnostics(bts_ctx* ctx) {
   if (ok) {                            // the one-row select with K_up (falls back to dense)
     ctx->plan_diag_u = fast_plan(1, ctx->d, ctx->K_up);
     ctx->fast_diag_u.dirty = &ctx->fast_diag_u_dirty;
+    ctx->fast_diag_u.calls = &ctx->fast_diag_u_calls;
     if (!alloc_fast(ctx, ctx->plan_diag_u, 1, &ctx->fast_diag_u)) {
       (void)hipGetLastError();
       ctx->plan_diag_u.enabled = false;
     }
+    ctx->fast_diag_v.dirty = &ctx->fast_diag_v_dirty;
+    ctx->fast_diag_v.calls = &ctx->fast_diag_v_calls;
+    ok = alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_diag_v);
   }
   if (ok && ctx->plan_up.enabled)      // partial sums of the rows' residual energies
     ok = dev_alloc(ctx, &ctx->fast_up.energy, (size_t)ctx->N * ctx->plan_up.nwc_pad) &&
@@ -467,7 +481,7 @@ int bidir_step_diag(bts_ctx* ctx, const float* g, float* eps, float* delta, floa
   }
   e = diag_after_step(ctx->stream, ctx->diag, ctx->dense, eps, delta, p, (uint32_t)ctx->N, ctx->d,
                       ctx->K_up, ctx->K_dn, alpha_in, up_idx, up_val, dn_idx, dn_val,
-                      agg_scratch(ctx), re, OneRowSelect{&ctx->plan_dn, &ctx->fast_dn},
+                      agg_scratch(ctx), re, OneRowSelect{&ctx->plan_dn, &ctx->fast_diag_v},
                       OneRowSelect{&ctx->plan_diag_u, &ctx->fast_diag_u}, diag);
   return e == hipSuccess ? BTS_OK : fail_hip(ctx, e);
 }
@@ -523,6 +537,7 @@ int bts_testing_mark_dirty(bts_ctx* ctx) {
   if (!ctx) return BTS_EINVAL;
   ctx->dense_dirty = true;
   ctx->fast_up_dirty = ctx->fast_dn_dirty = ctx->fast_diag_u_dirty = true;
+  ctx->fast_diag_v_dirty = true;
   ctx->mid_up_dirty = ctx->mid_dn_dirty = true;
   ctx->agg_tables_bad = true;
   return BTS_OK;

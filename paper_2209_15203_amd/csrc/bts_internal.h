@@ -67,9 +67,18 @@ struct DensePlan {
 };
 DensePlan dense_plan(const DenseScratch& sc, uint32_t rows, uint64_t d);
 hipError_t dense_begin(hipStream_t s, const DenseScratch& sc);
+// heal (all null = none): the single-pass select's bounds for its next call, which the
+// emission sets from the exact threshold for the rows it redoes (see cand_finish_body).
+struct NextBounds {
+  uint32_t* lower_key;
+  uint32_t* upper_key;     // written only if early_zero
+  uint32_t* prev_T;
+  bool early_zero;
+};
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
-                        float* out_val, RowMask need, FusedUpdate upd);
+                        float* out_val, RowMask need, FusedUpdate upd,
+                        NextBounds heal = NextBounds{nullptr, nullptr, nullptr, false});
 
 // x = fma(alpha, g, x) over rows x d and nothing else (K == 0).
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
@@ -89,6 +98,7 @@ struct FastPlan {
   uint32_t stride;         // every stride-th 256-coordinate slice is sampled
   uint32_t target;         // sampled coordinates wanted at or above the lower bound
   uint32_t target_u;       // K in sampled coordinates: aims the bound of the early zeroing
+  uint32_t rank_next;      // the next call's lower bound aims at this rank of the row (> K)
   uint32_t cap;            // capacity of one candidate list
   uint32_t stream_waves_per_simd;   // occupancy the dense pass is held to (3, 5 or 6)
   uint32_t ntiles;         // directory tiles (64 wave chunks) per row
@@ -99,6 +109,7 @@ struct FastScratch {
   uint32_t* sample_hist;   // rows x 8192 (zero between calls)
   uint32_t* lower_key;     // rows
   uint32_t* upper_key;     // rows: from which key on the dense pass stores +0 (see capture_chunk)
+  uint32_t* prev_T;        // rows: the threshold key the previous call found (0 = none)
   uint32_t* cand_cnt;      // rows x lists, one counter per 128-byte line
   uint2* cand;             // rows x lists x cap (index, value bits)
   uint32_t* hist;          // rows x fast_hist_words() partial histograms
@@ -108,6 +119,7 @@ struct FastScratch {
                            // of its run in its list and the run's length
   void* tile_cnt;          // rows x ntiles 64-bit words (rewritten by every call)
   bool* dirty;             // host flag: a call failed half way, clear directory and sample first
+  uint32_t* calls;         // host counter: calls since the bounds were last sampled from scratch
   uint32_t rows;           // rows the scratch was sized for
   // diagnostics only (null otherwise): fp64 sums of squares of what stays behind in the row,
   // per wave chunk (coordinates not captured) and per directory tile (captured, not kept)

@@ -188,6 +188,8 @@ __device__ __forceinline__ void capture_chunk(
 struct FastSel {
   uint32_t prefix, k_rem;     // key select in progress: first digit, keys wanted at or below it
   uint32_t T, r;              // threshold key; how many holders of T are kept
+  uint32_t U;                 // the dense pass of this call stored +0 where key >= U
+  uint32_t next_bin;          // first-digit bin of the entry at the rank the next call aims at
 };
 
 // ---- directory tiles -----------------------------------------------------------------------

@@ -53,7 +53,8 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
                                                  uint32_t nwc, uint32_t* __restrict__ out_idx,
                                                  float* __restrict__ out_val,
                                                  uint32_t* __restrict__ hist, RowMask need,
-                                                 bool streaming, FusedUpdate upd) {
+                                                 bool streaming, FusedUpdate upd,
+                                                 NextBounds heal) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_gt[kMaxShare], s_eq[kMaxShare];
   const uint32_t row = blockIdx.y;
@@ -61,6 +62,14 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
   if (blockIdx.x == 0)                             // leave the row's histograms clear
     for (int i = threadIdx.x; i < kRowHist; i += kBlock) hist[(uint64_t)row * kRowHist + i] = 0;
   const uint32_t T = st[row].T, r = st[row].r;
+  if (heal.lower_key != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+    // a row the single-pass select handed over: its next call starts from the exact
+    // threshold, a tenth below it in magnitude (finite, non-zero T; else from zero)
+    const bool plain = T != 0 && T < 0x7F800000u;
+    heal.lower_key[row] = plain ? __float_as_uint(__uint_as_float(T) * 0.9f) : 0u;
+    if (heal.early_zero) heal.upper_key[row] = T ? T : 0xFFFFFFFFu;
+    heal.prev_T[row] = 0;                          // no trend across a redo
+  }
   const VGrid vg{blockIdx.x, blockIdx.y, gridDim.x};
   const ChunkShare sh = block_share(vg, nwc);
   // kept before this share: every thread adds up some of the earlier shares' totals
@@ -231,12 +240,12 @@ hipError_t dense_begin(hipStream_t s, const DenseScratch& sc) {
 
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
-                        float* out_val, RowMask need, FusedUpdate upd) {
+                        float* out_val, RowMask need, FusedUpdate upd, NextBounds heal) {
   if (upd.w != nullptr && rows != 1) return hipErrorInvalidValue;
   const uint32_t nwc = pl.nwc;
   k_emit<<<dim3(pl.gx, rows), dim3(kBlock), 0, s>>>(x, d, K, sc.state, sc.cnt,
                                                     sc.block_sums, nwc, out_idx, out_val,
-                                                    sc.hist, need, pl.streaming, upd);
+                                                    sc.hist, need, pl.streaming, upd, heal);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   return hipSuccess;

@@ -302,44 +302,51 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist0(const uint2* __restri
 
 // The d0 bin holding the K-th largest entry from the blocks' partial histograms, coarse sums
 // first (256 x nparts words), then the 32 bins of the coarse bin found (32 x nparts words)
-// instead of all 8192 x nparts.  *above = entries in higher bins.  All threads call this.
+// instead of all 8192 x nparts.  *above = entries in higher bins.  In the same steps, with
+// the second wave of the block: *bin_next = the bin of the entry at rank `rank_next` (0 if
+// the lists hold fewer entries).  All threads call this (at least 256).
 __device__ __forceinline__ uint32_t resolve_d0(const uint32_t* __restrict__ part_row,
-                                               uint32_t nparts, uint32_t K, uint32_t* lds,
-                                               uint32_t* s_out, uint32_t* above) {
+                                               uint32_t nparts, uint32_t K, uint32_t rank_next,
+                                               uint32_t* lds, uint32_t* s_out, uint32_t* above,
+                                               uint32_t* bin_next) {
   const int cb = kD0Coarse - 1 - (int)threadIdx.x;        // this thread's coarse bin (if >= 0)
   uint32_t c = 0;
   if (cb >= 0)
     for (uint32_t b = 0; b < nparts; ++b) c += part_row[(uint64_t)b * kPartWords + kCoarseAt + cb];
   uint32_t total;
   const uint32_t excl = block_exclusive_scan(c, lds, &total);
-  if (threadIdx.x == 0) {
-    s_out[0] = 0;
-    s_out[1] = 0;
-  }
+  if (threadIdx.x < 4) s_out[threadIdx.x] = 0;
   __syncthreads();
   if (cb >= 0 && excl < K && K <= excl + c) {
     s_out[0] = (uint32_t)cb;
     s_out[1] = excl;
   }
+  if (cb >= 0 && excl < rank_next && rank_next <= excl + c) {
+    s_out[2] = (uint32_t)cb;
+    s_out[3] = excl;
+  }
   __syncthreads();
-  const uint32_t e = s_out[0], above_e = s_out[1];
+  const uint32_t which = threadIdx.x / kWave;             // wave 0: K, wave 1: rank_next
+  const uint32_t e = s_out[2 * (which & 1u)], above_e = s_out[2 * (which & 1u) + 1];
+  const uint32_t want = which == 0 ? K : rank_next;
   __syncthreads();
-  if (threadIdx.x < kWave) {
-    const int fb = kD0PerCoarse - 1 - (int)threadIdx.x;
+  if (which < 2) {
+    const int fb = kD0PerCoarse - 1 - (int)lane_id();
     uint32_t f = 0;
     if (fb >= 0)
       for (uint32_t b = 0; b < nparts; ++b)
         f += part_row[(uint64_t)b * kPartWords + e * kD0PerCoarse + fb];
     const uint32_t incl = wave_inclusive_scan(f);
     const uint32_t before = above_e + incl - f;
-    if (fb >= 0 && before < K && K <= before + f) {
-      s_out[0] = e * kD0PerCoarse + (uint32_t)fb;
-      s_out[1] = before;
+    if (fb >= 0 && before < want && want <= before + f) {
+      s_out[2 * which] = e * kD0PerCoarse + (uint32_t)fb;
+      s_out[2 * which + 1] = before;
     }
   }
   __syncthreads();
   const uint32_t bin = s_out[0];
   *above = s_out[1];
+  *bin_next = s_out[2];
   __syncthreads();
   return bin;
 }
@@ -374,6 +381,7 @@ __device__ __forceinline__ void restore_early_zeros(uint32_t row, const uint2* _
 __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restrict__ cand,
                                                        const uint32_t* __restrict__ cand_cnt,
                                                        uint32_t cap, uint32_t K,
+                                                       uint32_t rank_next,
                                                        const uint32_t* __restrict__ lower_key,
                                                        const uint32_t* __restrict__ upper_key,
                                                        uint32_t* __restrict__ partial,
@@ -382,15 +390,16 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
                                                        float* __restrict__ x, uint64_t d) {
   __shared__ uint32_t sh[kD1Bins];
   __shared__ uint32_t lds[kCandBlock / kWave + 1];
-  __shared__ uint32_t s_out[2];
+  __shared__ uint32_t s_out[4];
   const uint32_t row = blockIdx.y;
   if (need[row] == 1u) {                   // set by the previous kernel; 2 is set below
     restore_early_zeros(row, cand, cand_cnt, cap, upper_key[row], x, d);
     return;
   }
   uint32_t* part_row = partial + (uint64_t)row * gridDim.x * kPartWords;
-  uint32_t above;
-  const uint32_t b0 = resolve_d0(part_row, gridDim.x, K, lds, s_out, &above);
+  uint32_t above, bin_next;
+  const uint32_t b0 = resolve_d0(part_row, gridDim.x, K, rank_next, lds, s_out, &above,
+                                 &bin_next);
   if (b0 == (uint32_t)kD0Bins - 1) {       // T is beyond the window: the dense path redoes the row
     if (blockIdx.x == 0 && threadIdx.x == 0) need[row] = 2u;
     restore_early_zeros(row, cand, cand_cnt, cap, upper_key[row], x, d);
@@ -399,6 +408,7 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     sel[row].prefix = b0;
     sel[row].k_rem = K - above;
+    sel[row].next_bin = bin_next;
   }
   for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) sh[i] = 0;
   __syncthreads();
@@ -429,23 +439,61 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
   for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) out[i] = sh[i];
 }
 
+// Also sets the row's bounds for the NEXT call on this scratch, which then needs no sample:
+// the threshold moves little from one step of the training to the next, and this call knows
+// it exactly.  The lower bound becomes the key this call found at rank rank_next (a rank
+// beyond K, so that about rank_next - K spare candidates are listed), the bound of the early
+// zeroing becomes the threshold itself, both moved along with the relative change of the
+// threshold over the last call (the residuals of a young run grow from step to step, ever
+// more slowly): the zeroing bound by 0.8 of it, which is about unbiased for such a run, the
+// lower bound by half of it, which errs towards more candidates.  A wrong guess costs time,
+// never the result: the next call verifies its lists like any other and hands a row whose
+// lists fall short or overflow to the dense path, whose emission sets the row's bounds from
+// its exact threshold instead (k_emit).
 __device__ __forceinline__ void cand_finish_body(uint32_t row,
                                                  const uint32_t* __restrict__ partial,
-                                                 uint32_t nparts,
-                                                 const uint32_t* __restrict__ lower_key,
+                                                 uint32_t nparts, bool early_zero,
+                                                 uint32_t* __restrict__ lower_key,
+                                                 uint32_t* __restrict__ upper_key,
+                                                 uint32_t* __restrict__ prev_T,
+                                                 uint32_t* __restrict__ cand_cnt,
                                                  FastSel* __restrict__ sel,
                                                  const uint32_t* __restrict__ need) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_out[2];
+  // the lists are read through the directory from here on: counters clear for the next call
+  if (threadIdx.x < kSubLists)
+    cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride] = 0;
   if (need[row]) return;
   const FastSel s = sel[row];
+  const uint32_t* part_row = partial + (uint64_t)row * nparts * kPartWords;
   uint32_t above;
-  const uint32_t b1 = resolve_bins<kD1Bins, kBlock>(
-      partial + (uint64_t)row * nparts * kPartWords + kD0Bins, nparts, kPartWords, s.k_rem, lds,
-      s_out, &above);
+  const uint32_t b1 = resolve_bins<kD1Bins, kBlock>(part_row + kD0Bins, nparts, kPartWords,
+                                                    s.k_rem, lds, s_out, &above);
   if (threadIdx.x == 0) {
-    sel[row].T = lower_key[row] + ((s.prefix << kD1Bits) | b1);
+    const uint32_t b_next = s.next_bin;    // first-digit bin of the entry at rank rank_next
+    const uint32_t L = lower_key[row];
+    const uint32_t T = L + ((s.prefix << kD1Bits) | b1);
+    sel[row].T = T;
     sel[row].r = s.k_rem - above;
+    sel[row].U = early_zero ? upper_key[row] : kNeverKey;
+    uint32_t key_next = L + (b_next << kD1Bits);           // <= T: rank_next > K
+    if (key_next > T) key_next = T;
+    const uint32_t was = prev_T[row];
+    uint32_t L_next = key_next, U_next = T;
+    if (T != 0 && T < 0x7F800000u) {                       // finite, non-zero: magnitudes scale
+      float change = 0.0f;
+      if (was != 0 && was < 0x7F800000u) {
+        change = __uint_as_float(T) / __uint_as_float(was) - 1.0f;
+        change = fminf(fmaxf(change, -0.2f), 0.5f);
+      }
+      L_next = __float_as_uint(__uint_as_float(key_next) * (1.0f + 0.5f * change)) & 0x7FFFFFFFu;
+      U_next = __float_as_uint(__uint_as_float(T) * (1.0f + 0.8f * change)) & 0x7FFFFFFFu;
+      if (L_next > U_next) L_next = U_next;
+    }
+    lower_key[row] = L_next;
+    if (early_zero) upper_key[row] = U_next;
+    prev_T[row] = T;
   }
 }
 
@@ -548,7 +596,7 @@ template <int TPW>
 __device__ __forceinline__ void dir_emit_body(
     uint32_t bx, uint32_t row, uint2* __restrict__ dir, uint32_t nwc_pad,
     const uint2* __restrict__ cand, uint32_t cap, const FastSel* __restrict__ sel,
-    const uint32_t* __restrict__ upper_key, const uint32_t* __restrict__ need,
+    const uint32_t* __restrict__ need,
     const unsigned long long* __restrict__ tile_cnt, uint32_t ntiles, float* __restrict__ x,
     uint64_t d, uint32_t K, uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
     double* __restrict__ tile_energy, FusedUpdate upd) {
@@ -567,7 +615,7 @@ __device__ __forceinline__ void dir_emit_body(
   }
   if (need[row]) return;
   const FastSel s = sel[row];
-  const uint32_t U = upper_key[row];       // the dense pass stored +0 where key >= U
+  const uint32_t U = s.U;                  // the dense pass stored +0 where key >= U
   const uint2* cand_row = cand + (uint64_t)row * kSubLists * cap;
   float* xr = x + (uint64_t)row * d;
   uint32_t* oi = out_idx + (uint64_t)row * K;
@@ -653,11 +701,14 @@ __device__ __forceinline__ VGrid dense_vgrid(uint32_t b, const DensePart& dp) {
 }
 
 __global__ __launch_bounds__(kBlock) void k_finish_hist0(uint32_t own, const uint32_t* partial,
-                                                         uint32_t nparts,
-                                                         const uint32_t* lower_key, FastSel* sel,
+                                                         uint32_t nparts, bool early_zero,
+                                                         uint32_t* lower_key,
+                                                         uint32_t* upper_key, uint32_t* prev_T,
+                                                         uint32_t* cand_cnt, FastSel* sel,
                                                          const uint32_t* need, DensePart dp) {
   if (blockIdx.x < own)
-    cand_finish_body(blockIdx.x, partial, nparts, lower_key, sel, need);
+    cand_finish_body(blockIdx.x, partial, nparts, early_zero, lower_key, upper_key,
+                     prev_T, cand_cnt, sel, need);
   else
     hist_body<0, false>(dense_vgrid(blockIdx.x - own, dp), nullptr, dp.x, dp.d, 0.0f, dp.K,
                         dp.hist, dp.nwc, need, dp.streaming);
@@ -690,12 +741,12 @@ __global__ __launch_bounds__(kBlock) void k_dirscan_hist2(uint32_t own,
 template <int TPW>
 __global__ __launch_bounds__(kBlock) void k_diremit_count(
     uint32_t own, uint32_t own_gx, uint2* dir, uint32_t nwc_pad, const uint2* cand, uint32_t cap,
-    const FastSel* sel, const uint32_t* upper_key, const uint32_t* need,
+    const FastSel* sel, const uint32_t* need,
     const unsigned long long* tile_cnt, uint32_t ntiles, uint32_t* out_idx, float* out_val,
     double* tile_energy, FusedUpdate upd, DensePart dp) {
   if (blockIdx.x < own)
     dir_emit_body<TPW>(blockIdx.x % own_gx, blockIdx.x / own_gx, dir, nwc_pad, cand, cap, sel,
-                       upper_key, need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val,
+                       need, tile_cnt, ntiles, dp.x, dp.d, dp.K, out_idx, out_val,
                        tile_energy, upd);
   else
     count_body(dense_vgrid(blockIdx.x - own, dp), dp.x, dp.d, dp.K, dp.hist, dp.state,
@@ -752,6 +803,9 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
   p.target = (uint32_t)target;
   p.target_u = (uint32_t)((K + stride / 2) / stride);   // K coordinates of the row, in samples
   if (p.target_u < 1) p.target_u = 1;
+  // bounds handed from call to call: a quarter spare candidates, at least 256 (the count at
+  // a fixed bound moves by its square root from step to step, and by the drift of the run)
+  p.rank_next = K + (K / 4 > 256 ? K / 4 : 256);
   p.cap = (uint32_t)cap;
   // How many waves per SIMD the dense pass is held to (a kernel variant whose register
   // allocation admits no more): a stream of 2 reads : 1 write runs best well below full
@@ -784,25 +838,31 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
     hipError_t e = fill_u32(s, reinterpret_cast<uint32_t*>(sc.dir),
                             (uint64_t)sc.rows * pl.nwc_pad * 2, 0);
     if (e == hipSuccess) e = fill_u32(s, sc.sample_hist, (uint64_t)sc.rows * kSampleBins, 0);
+    if (e == hipSuccess) e = fill_u32(s, sc.prev_T, sc.rows, 0);
     if (e != hipSuccess) return e;
   }
+  // 1. bounds: from a sample on the scratch's first two calls and after a failed one; later
+  // calls start from the bounds the call before them left (see cand_finish_body)
+  if (*sc.dirty) *sc.calls = 0;
+  const bool sampled = *sc.calls < 2;
   *sc.dirty = true;      // cleared when every launch of this call went out
-  // 1. sample
-  const uint64_t n_samp = (d / 256) / pl.stride + 1;
-  uint32_t sample_blocks = (uint32_t)((n_samp + kWavesPerBlock * 8 - 1) / (kWavesPerBlock * 8));
-  if (sample_blocks > 64) sample_blocks = 64;
-  if (sample_blocks < 1) sample_blocks = 1;
-  if (g != nullptr)
-    k_sample_hist<true><<<dim3(sample_blocks, rows), block, 0, s>>>(g, x, d, alpha, pl.stride,
-                                                                    sc.sample_hist);
-  else
-    k_sample_hist<false><<<dim3(sample_blocks, rows), block, 0, s>>>(nullptr, x, d, 0.0f,
-                                                                     pl.stride, sc.sample_hist);
-  BTS_LAUNCH_CHECK();
-  k_pick_bound<<<dim3(rows), block, 0, s>>>(sc.sample_hist, pl.target,
-                                            g != nullptr ? pl.target_u : 0u, sc.lower_key,
-                                            sc.upper_key, sc.cand_cnt);
-  BTS_LAUNCH_CHECK();
+  if (sampled) {
+    const uint64_t n_samp = (d / 256) / pl.stride + 1;
+    uint32_t sample_blocks = (uint32_t)((n_samp + kWavesPerBlock * 8 - 1) / (kWavesPerBlock * 8));
+    if (sample_blocks > 64) sample_blocks = 64;
+    if (sample_blocks < 1) sample_blocks = 1;
+    if (g != nullptr)
+      k_sample_hist<true><<<dim3(sample_blocks, rows), block, 0, s>>>(g, x, d, alpha, pl.stride,
+                                                                      sc.sample_hist);
+    else
+      k_sample_hist<false><<<dim3(sample_blocks, rows), block, 0, s>>>(nullptr, x, d, 0.0f,
+                                                                       pl.stride, sc.sample_hist);
+    BTS_LAUNCH_CHECK();
+    k_pick_bound<<<dim3(rows), block, 0, s>>>(sc.sample_hist, pl.target,
+                                              g != nullptr ? pl.target_u : 0u, sc.lower_key,
+                                              sc.upper_key, sc.cand_cnt);
+    BTS_LAUNCH_CHECK();
+  }
   // 2. the dense pass (a wave of the grid may lie past the row's last chunk, never past
   // the padded directory)
   if (ev0) (void)hipEventRecord(ev0, s);
@@ -835,8 +895,9 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   k_cand_hist0<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
                                                   sc.hist, sc.need);
   BTS_LAUNCH_CHECK();
-  k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, sc.lower_key,
-                                                  sc.upper_key, sc.hist, sel, sc.need, x, d);
+  k_cand_hist1<<<hgrid, dim3(kCandBlock), 0, s>>>(sc.cand, sc.cand_cnt, pl.cap, K, pl.rank_next,
+                                                  sc.lower_key, sc.upper_key, sc.hist, sel,
+                                                  sc.need, x, d);
   BTS_LAUNCH_CHECK();
   // 4 (rest) + 5 + the first four kernels of the gated dense redo, pair by pair
   const DensePlan dpl = dense_plan(dense, rows, d);
@@ -861,7 +922,9 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   if (tile_blocks + dense_blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   const dim3 grid_rows((unsigned)(rows + dense_blocks));
   const dim3 grid_tiles((unsigned)(tile_blocks + dense_blocks));
-  k_finish_hist0<<<grid_rows, block, 0, s>>>(rows, sc.hist, hb, sc.lower_key, sel, sc.need, dp);
+  k_finish_hist0<<<grid_rows, block, 0, s>>>(rows, sc.hist, hb, g != nullptr,
+                                             sc.lower_key, sc.upper_key, sc.prev_T, sc.cand_cnt,
+                                             sel, sc.need, dp);
   BTS_LAUNCH_CHECK();
   if (sparse_tiles)
     k_dircount_hist1<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
@@ -876,18 +939,20 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   BTS_LAUNCH_CHECK();
   if (sparse_tiles)
     k_diremit_count<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
-                                                    pl.nwc_pad, sc.cand, pl.cap, sel,
-                                                    sc.upper_key, sc.need, tile_cnt, pl.ntiles,
-                                                    out_idx, out_val, tile_energy, upd, dp);
+                                                    pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                                    tile_cnt, pl.ntiles, out_idx, out_val,
+                                                    tile_energy, upd, dp);
   else
     k_diremit_count<1><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
-                                                    pl.nwc_pad, sc.cand, pl.cap, sel,
-                                                    sc.upper_key, sc.need, tile_cnt, pl.ntiles,
-                                                    out_idx, out_val, tile_energy, upd, dp);
+                                                    pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
+                                                    tile_cnt, pl.ntiles, out_idx, out_val,
+                                                    tile_energy, upd, dp);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
-  // the rest of the redo: scan of the per-chunk counts, emission of the flagged rows
-  return dense_finish(s, dense, dpl, x, rows, d, K, out_idx, out_val, sc.need, upd);
+  *sc.calls += 1;
+  // the rest of the redo: emission of the flagged rows, which also sets their next bounds
+  return dense_finish(s, dense, dpl, x, rows, d, K, out_idx, out_val, sc.need, upd,
+                      NextBounds{sc.lower_key, sc.upper_key, sc.prev_T, g != nullptr});
 }
 
 size_t fast_sel_bytes() { return sizeof(FastSel); }
