@@ -226,14 +226,30 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
   if (total <= kLdsEntries) {
     // ---- the candidates fit in LDS: gather them in index order, do the rest there ----------
     uint2* s_ent = reinterpret_cast<uint2*>(pool);
-    for (uint32_t c = c0; c < c1; ++c) {
-      const uint2 ent = dir_row[c];
-      if (ent.y == 0) continue;
-      dir_row[c] = make_uint2(0u, 0u);             // leave the directory clear
-      const uint2* run = cand_row + (uint64_t)(c % kSubLists) * cap + ent.x;
-      for (uint32_t j = 0; j < ent.y; ++j)
-        if (at + j < kLdsEntries) s_ent[at + j] = run[j];
-      at += ent.y;
+    // four chunks at a time: their directory entries, then the first entry of each run (most
+    // runs hold one entry where K is a thousandth of d), loaded together; longer runs after
+    for (uint32_t cb = c0; cb < c1; cb += 4) {
+      uint2 ent[4], first[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        ent[u] = cb + u < c1 ? dir_row[cb + u] : make_uint2(0u, 0u);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        first[u] = make_uint2(0u, 0u);
+        if (ent[u].y) {
+          dir_row[cb + u] = make_uint2(0u, 0u);    // leave the directory clear
+          first[u] = cand_row[(uint64_t)((cb + u) % kSubLists) * cap + ent[u].x];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (ent[u].y == 0) continue;
+        if (at < kLdsEntries) s_ent[at] = first[u];
+        const uint2* run = cand_row + (uint64_t)((cb + u) % kSubLists) * cap + ent[u].x;
+        for (uint32_t j = 1; j < ent[u].y; ++j)
+          if (at + j < kLdsEntries) s_ent[at + j] = run[j];
+        at += ent[u].y;
+      }
     }
     for (int i = t; i < kHiBins; i += kMidBlock) sh[i] = 0;
     __syncthreads();
@@ -256,7 +272,10 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
     const uint32_t lo = resolve_bins<kLoBins, kMidBlock>(sh, 1, 0, k_rem, lds, s_out, &above);
     const uint32_t T = L + ((hi << kLoBits) | lo);   // the exact K-th largest key
     const uint32_t r = k_rem - above;                // holders of T that are kept
-    // ordered emission, 1024 entries at a time
+    // ordered emission, 1024 entries at a time.  The emitted indices also go to LDS, over
+    // the entries already emitted (the message grows no faster than the entries are read:
+    // 4 bytes at pos <= e against 8 at e), for the range table below.
+    uint32_t* s_idx = pool;
     uint32_t run_gt = 0, run_eq = 0;
     for (uint32_t e0 = 0; e0 < total; e0 += kMidBlock) {
       const uint32_t e = e0 + t;
@@ -281,6 +300,7 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
       }
       if (is_gt || (is_eq && n_eq < r)) {
         const uint32_t pos = n_gt + min(n_eq, r);
+        if (pos < K) s_idx[pos] = en.x;
         if (pos < K && en.x < d) {
           const float val = __uint_as_float(en.y);
           oi[pos] = en.x;
@@ -420,15 +440,17 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
     // it if its successor does; the opener also raises the range's flag.  The message was
     // written by this workgroup: after the barrier its own stores are visible to it.
     __syncthreads();
+    // the message's indices: from LDS where the emission left them there, else from memory
+    const uint32_t* msg = total <= kLdsEntries ? pool : oi;
     for (uint32_t j = t; j < K; j += kMidBlock) {
-      const uint32_t i = oi[j];
+      const uint32_t i = msg[j];
       if (i >= d) continue;
       const uint32_t rg = i / kAggWidth;
-      if (j == 0 || oi[j - 1] / kAggWidth != rg) {
+      if (j == 0 || msg[j - 1] / kAggWidth != rg) {
         tab_start[(uint64_t)rg * N + row] = j;
         tab_any[rg] = 1u;
       }
-      if (j + 1 == K || oi[j + 1] / kAggWidth != rg) tab_end[(uint64_t)rg * N + row] = j + 1;
+      if (j + 1 == K || msg[j + 1] / kAggWidth != rg) tab_end[(uint64_t)rg * N + row] = j + 1;
     }
   }
 }
