@@ -160,3 +160,40 @@ def test_diag_step_checks_every_argument_before_it_queues_anything():
     assert call(ptr(w), ptr(ui), ptr(eps)) == 0
     torch.cuda.synchronize()
     assert float(diag[3]) >= 0.0
+
+
+def test_bounds_handed_from_call_to_call_never_decide_the_result(oracle):
+    """From its third call on a context's single-pass select starts from bounds the call
+    before left behind instead of sampling.  The gradients' scale jumps by factors of 50
+    between calls here, so those bounds are far off in both directions (lists that overflow,
+    lists that fall short, coordinates zeroed early that are not sent after all): every call
+    must still match the oracle bit for bit, and once the scale holds still the rows must
+    finish in the single pass again (the redo sets a row's bounds from its exact threshold)."""
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(4242)
+    N, d, K = 3, 300_007, 600
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    ctx.set_path(2)
+    eps = np.zeros((N, d), np.float32)
+    te = torch.from_numpy(eps).to(D)
+    ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+    scales = [1.0, 1.0, 1.0, 50.0, 1.0, 0.02, 0.02, 0.02, 0.02, 30.0, 30.0, 30.0]
+    paths = []
+    for step, sc in enumerate(scales):
+        g = (rng.standard_normal((N, d)) * sc).astype(np.float32)
+        if step == 5:
+            eps[:] = 0.0                # forget the large residuals, so that the scale can drop
+            te.zero_()
+        bts.topk_compress(ctx, torch.from_numpy(g).to(D), te, 0.5, ui, uv)
+        torch.cuda.synchronize()
+        wi, wv = oracle.worker_stage(g, eps, 0.5, K)
+        G.assert_same_bits(ui, wi, f"step {step} up_idx")
+        G.assert_same_bits(uv, wv, f"step {step} up_val")
+        G.assert_same_bits(te, eps, f"step {step} eps")
+        paths.append(ctx.last_path(0))
+    assert paths[0] == (N, 0) and paths[1] == (N, 0) and paths[2] == (N, 0), paths
+    assert any(p[1] > 0 for p in paths[3:7]), f"the jumps should have sent rows to the redo: {paths}"
+    assert paths[8] == (N, 0) and paths[11] == (N, 0), f"bounds did not recover: {paths}"
