@@ -225,7 +225,14 @@ int downlink_and_update(bts_ctx* ctx, float* delta, uint32_t* dn_idx, float* dn_
                         float alpha_out, float* w) {
   if (ctx->K_dn <= 4096)
     return run_select(ctx, false, nullptr, delta, 0.0f, dn_idx, dn_val, nullptr,
-                      FusedUpdate{w, -alpha_out});
+                      FusedUpdate{w, -alpha_out, false});
+  // a longer message on the single-pass path: applied, one pair per thread, in the select's
+  // last launch, whose workgroups are idle unless the row needs the dense redo
+  const bool single_pass = !(ctx->path_mode == 0 && row_select_fits(ctx->d)) &&
+                           !use_mid(ctx, ctx->mid_plan_dn) && use_fast(ctx, ctx->plan_dn);
+  if (single_pass)
+    return run_select(ctx, false, nullptr, delta, 0.0f, dn_idx, dn_val, nullptr,
+                      FusedUpdate{w, -alpha_out, true});
   const int rc = run_select(ctx, false, nullptr, delta, 0.0f, dn_idx, dn_val);
   if (rc != BTS_OK) return rc;
   return sparse_sgd_update(ctx, dn_idx, dn_val, ctx->K_dn, alpha_out, w);

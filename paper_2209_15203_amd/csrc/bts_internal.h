@@ -26,9 +26,14 @@ struct SelState {
 // Model update line of Algorithm 2 fused into the emission of a ONE-ROW select (the server's
 // compression): the lane that writes the pair (i, v) of the message also does
 // w[i] = fma(neg_alpha, v, w[i]).  w == nullptr: no update.
+// after (single-pass select only): the update is not done by the emitting lanes but from the
+// finished message, one pair per thread, in the select's last launch (the emission of the
+// gated dense redo, whose workgroups are idle for a row that needs no redo; a row that does
+// is updated by the redo's emitting lanes).
 struct FusedUpdate {
   float* w;
   float neg_alpha;
+  bool after;
 };
 
 // Rows that a gated kernel must process (null pointer = all rows).
@@ -79,6 +84,7 @@ hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& 
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
                         float* out_val, RowMask need, FusedUpdate upd,
                         NextBounds heal = NextBounds{nullptr, nullptr, nullptr, false});
+// (upd.after: rows that need no redo are updated from their finished message instead)
 
 // x = fma(alpha, g, x) over rows x d and nothing else (K == 0).
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,

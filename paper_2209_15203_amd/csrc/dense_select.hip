@@ -58,7 +58,16 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_gt[kMaxShare], s_eq[kMaxShare];
   const uint32_t row = blockIdx.y;
-  if (!row_needed(need, row)) return;
+  if (!row_needed(need, row)) {
+    if (upd.w != nullptr && upd.after) {           // the finished message of a one-row select
+      for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < K; j += gridDim.x * kBlock) {
+        const uint32_t i = out_idx[(uint64_t)row * K + j];
+        if (i < d)
+          upd.w[i] = __fmaf_rn(upd.neg_alpha, out_val[(uint64_t)row * K + j], upd.w[i]);
+      }
+    }
+    return;
+  }
   if (blockIdx.x == 0)                             // leave the row's histograms clear
     for (int i = threadIdx.x; i < kRowHist; i += kBlock) hist[(uint64_t)row * kRowHist + i] = 0;
   const uint32_t T = st[row].T, r = st[row].r;

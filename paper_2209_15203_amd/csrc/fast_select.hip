@@ -828,6 +828,8 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                        const DenseScratch& dense, bool energy, FusedUpdate upd) {
   const dim3 block(kBlock);
   if (upd.w != nullptr && rows != 1) return hipErrorInvalidValue;
+  // the update done by the emitting lanes, or after the emission (see FusedUpdate)
+  const FusedUpdate emit_upd = upd.after ? FusedUpdate{nullptr, 0.0f, false} : upd;
   if (energy && (g == nullptr || sc.energy == nullptr || sc.tile_energy == nullptr))
     return hipErrorInvalidValue;
   double* tile_energy = energy ? sc.tile_energy : nullptr;
@@ -941,12 +943,12 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
     k_diremit_count<4><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
                                                     pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
                                                     tile_cnt, pl.ntiles, out_idx, out_val,
-                                                    tile_energy, upd, dp);
+                                                    tile_energy, emit_upd, dp);
   else
     k_diremit_count<1><<<grid_tiles, block, 0, s>>>((uint32_t)tile_blocks, tgx, sc.dir,
                                                     pl.nwc_pad, sc.cand, pl.cap, sel, sc.need,
                                                     tile_cnt, pl.ntiles, out_idx, out_val,
-                                                    tile_energy, upd, dp);
+                                                    tile_energy, emit_upd, dp);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   *sc.calls += 1;
