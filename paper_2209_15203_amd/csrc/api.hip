@@ -205,8 +205,14 @@ int run_select(bts_ctx* ctx, bool uplink, const float* g, float* x, float alpha,
     }
     e = mid_select(ctx->stream, ms, mp, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1, upd, mr);
   } else if (use_fast(ctx, pl)) {
+    MidRanges mr{nullptr, nullptr, nullptr};
+    const AggScratch as = agg_scratch(ctx);
+    if (want_ranges && as.tab_start != nullptr) {
+      mr = MidRanges{as.tab_start, as.tab_end, as.any};
+      *ranges = true;
+    }
     e = fast_select(ctx->stream, fs, pl, g, x, rows, ctx->d, K, alpha, idx, val, e0, e1,
-                    ctx->dense, want_energy, upd);
+                    ctx->dense, want_energy, upd, mr);
     if (energy != nullptr) *energy = want_energy;
   } else {
     e = dense_select(ctx->stream, ctx->dense, g, x, rows, ctx->d, K, alpha, idx, val, nullptr,

@@ -36,6 +36,20 @@ struct FusedUpdate {
   bool after;
 };
 
+constexpr uint32_t kAggWidth = 1024;   // coordinates per range of the aggregation
+
+// The aggregation's range tables (ranges x N entries each, all zero between calls), filled
+// for the worker rows by the select's last kernel so that the aggregation needs no pass of
+// its own over the messages (null: not wanted).  For worker q and range r, tab_start holds
+// K - (the first pair of q's message inside r), tab_end one past the last such pair; zero =
+// the message does not enter the range.  (The start counts down from K so that both entries
+// can be built with atomic maxima on zeroed memory where pairs arrive in no order.)
+struct MidRanges {
+  uint32_t* tab_start;
+  uint32_t* tab_end;
+  uint32_t* any;           // per range: somebody names it
+};
+
 // Rows that a gated kernel must process (null pointer = all rows).
 using RowMask = const uint32_t*;
 
@@ -83,8 +97,11 @@ struct NextBounds {
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
                         float* out_val, RowMask need, FusedUpdate upd,
-                        NextBounds heal = NextBounds{nullptr, nullptr, nullptr, false});
-// (upd.after: rows that need no redo are updated from their finished message instead)
+                        NextBounds heal = NextBounds{nullptr, nullptr, nullptr, false},
+                        MidRanges ranges = MidRanges{nullptr, nullptr, nullptr});
+// (upd.after: rows that need no redo are updated from their finished message instead;
+// ranges, with a row mask only: the emission's launch also fills the range tables, for the
+// rows that need no redo from their finished messages, for the others pair by pair)
 
 // x = fma(alpha, g, x) over rows x d and nothing else (K == 0).
 hipError_t axpy_only(hipStream_t s, const float* g, float* x, uint32_t rows, uint64_t d,
@@ -146,7 +163,8 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
                        const DenseScratch& dense, bool energy,
-                       FusedUpdate upd = FusedUpdate{nullptr, 0.0f});
+                       FusedUpdate upd = FusedUpdate{nullptr, 0.0f},
+                       MidRanges ranges = MidRanges{nullptr, nullptr, nullptr});
 
 // ---- middling rows, small K: three launches, no fallback (mid_select.hip) ------------------
 struct MidPlan {
@@ -167,13 +185,6 @@ struct MidScratch {
   bool* dirty;             // host flag: a call failed half way, clear the scratch first
   uint32_t rows;           // rows the scratch was sized for
 };
-// The aggregation's range tables, filled for the worker rows by the select's last kernel so
-// that the aggregation needs no pass of its own over the messages (null: not wanted).
-struct MidRanges {
-  uint32_t* tab_start;
-  uint32_t* tab_end;
-  uint32_t* any;
-};
 MidPlan mid_plan(uint32_t rows, uint64_t d, uint32_t K);
 size_t mid_bound_bytes();
 uint32_t mid_hist_words();
@@ -184,7 +195,6 @@ hipError_t mid_select(hipStream_t s, const MidScratch& sc, const MidPlan& pl, co
                       FusedUpdate upd, const MidRanges& ranges);
 
 // ---- server side ------------------------------------------------------------------------
-constexpr uint32_t kAggWidth = 1024;   // coordinates per range of the aggregation
 uint32_t aggregate_ranges(uint64_t d);
 uint32_t aggregate_scratch_words(uint64_t d);
 struct AggScratch {

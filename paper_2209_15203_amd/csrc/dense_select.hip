@@ -54,11 +54,26 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
                                                  float* __restrict__ out_val,
                                                  uint32_t* __restrict__ hist, RowMask need,
                                                  bool streaming, FusedUpdate upd,
-                                                 NextBounds heal) {
+                                                 NextBounds heal, MidRanges ranges) {
   __shared__ uint32_t lds[kBlock / kWave + 1];
   __shared__ uint32_t s_gt[kMaxShare], s_eq[kMaxShare];
   const uint32_t row = blockIdx.y;
   if (!row_needed(need, row)) {
+    if (ranges.tab_start != nullptr) {             // the finished message of a worker row
+      const uint32_t* msg = out_idx + (uint64_t)row * K;
+      const uint32_t N = gridDim.y;
+      for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < K; j += gridDim.x * kBlock) {
+        const uint32_t i = msg[j];
+        if (i >= d) continue;
+        const uint32_t rg = i / kAggWidth;
+        if (j == 0 || msg[j - 1] / kAggWidth != rg) {
+          ranges.tab_start[(uint64_t)rg * N + row] = K - j;
+          ranges.any[rg] = 1u;
+        }
+        if (j + 1 == K || msg[j + 1] / kAggWidth != rg)
+          ranges.tab_end[(uint64_t)rg * N + row] = j + 1;
+      }
+    }
     if (upd.w != nullptr && upd.after) {           // the finished message of a one-row select
       for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < K; j += gridDim.x * kBlock) {
         const uint32_t i = out_idx[(uint64_t)row * K + j];
@@ -157,6 +172,12 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
               oi[pos] = i;
               ov[pos] = v[j];
               x[e + j] = 0.0f;
+              if (ranges.tab_start != nullptr) {   // pairs arrive in no order: maxima
+                const uint64_t at = (uint64_t)(i / kAggWidth) * gridDim.y + row;
+                atomicMax(&ranges.tab_start[at], K - pos);
+                atomicMax(&ranges.tab_end[at], pos + 1);
+                ranges.any[i / kAggWidth] = 1u;
+              }
               if (upd.w != nullptr) upd.w[i] = __fmaf_rn(upd.neg_alpha, v[j], upd.w[i]);
             }
           }
@@ -249,12 +270,15 @@ hipError_t dense_begin(hipStream_t s, const DenseScratch& sc) {
 
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
-                        float* out_val, RowMask need, FusedUpdate upd, NextBounds heal) {
+                        float* out_val, RowMask need, FusedUpdate upd, NextBounds heal,
+                        MidRanges ranges) {
+  if (ranges.tab_start != nullptr && need == nullptr) return hipErrorInvalidValue;
   if (upd.w != nullptr && rows != 1) return hipErrorInvalidValue;
   const uint32_t nwc = pl.nwc;
   k_emit<<<dim3(pl.gx, rows), dim3(kBlock), 0, s>>>(x, d, K, sc.state, sc.cnt,
                                                     sc.block_sums, nwc, out_idx, out_val,
-                                                    sc.hist, need, pl.streaming, upd, heal);
+                                                    sc.hist, need, pl.streaming, upd, heal,
+                                                    ranges);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
   return hipSuccess;

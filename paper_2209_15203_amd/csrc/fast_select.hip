@@ -825,7 +825,8 @@ FastPlan fast_plan(uint32_t rows, uint64_t d, uint32_t K) {
 hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl, const float* g,
                        float* x, uint32_t rows, uint64_t d, uint32_t K, float alpha,
                        uint32_t* out_idx, float* out_val, hipEvent_t ev0, hipEvent_t ev1,
-                       const DenseScratch& dense, bool energy, FusedUpdate upd) {
+                       const DenseScratch& dense, bool energy, FusedUpdate upd,
+                       MidRanges ranges) {
   const dim3 block(kBlock);
   if (upd.w != nullptr && rows != 1) return hipErrorInvalidValue;
   // the update done by the emitting lanes, or after the emission (see FusedUpdate)
@@ -954,7 +955,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   *sc.calls += 1;
   // the rest of the redo: emission of the flagged rows, which also sets their next bounds
   return dense_finish(s, dense, dpl, x, rows, d, K, out_idx, out_val, sc.need, upd,
-                      NextBounds{sc.lower_key, sc.upper_key, sc.prev_T, g != nullptr});
+                      NextBounds{sc.lower_key, sc.upper_key, sc.prev_T, g != nullptr}, ranges);
 }
 
 size_t fast_sel_bytes() { return sizeof(FastSel); }

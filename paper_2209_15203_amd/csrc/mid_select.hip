@@ -447,7 +447,7 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
       if (i >= d) continue;
       const uint32_t rg = i / kAggWidth;
       if (j == 0 || msg[j - 1] / kAggWidth != rg) {
-        tab_start[(uint64_t)rg * N + row] = j;
+        tab_start[(uint64_t)rg * N + row] = K - j;
         tab_any[rg] = 1u;
       }
       if (j + 1 == K || msg[j + 1] / kAggWidth != rg) tab_end[(uint64_t)rg * N + row] = j + 1;

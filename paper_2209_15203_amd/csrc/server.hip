@@ -48,7 +48,7 @@ __global__ void k_range_bounds(const uint32_t* __restrict__ up_idx, uint32_t N, 
   if (row[j] >= d) return;                       // invalid input never reaches the table
   const uint32_t r = row[j] / kAggWidth;
   if (j == 0 || row[j - 1] / kAggWidth != r) {
-    start[(uint64_t)r * N + q] = j;
+    start[(uint64_t)r * N + q] = K_up - j;      // counted down from K_up: zero = none
     any[r] = 1u;
   }
   if (j + 1 == K_up || row[j + 1] / kAggWidth != r) end[(uint64_t)r * N + q] = j + 1;
@@ -117,10 +117,11 @@ __device__ __forceinline__ uint32_t aggregate_range(
       if (tab_start != nullptr) {
         const uint64_t at = (uint64_t)r * N + q0 + lane;
         const bool ready = q0 == 0 && pf.valid;
-        lo = ready ? pf.lo : tab_start[at];
+        const uint32_t lo_down = ready ? pf.lo : tab_start[at];   // K_up - first pair, 0 = none
         const uint32_t hi = ready ? pf.hi : tab_end[at];
-        n = (hi > lo && hi <= K_up) ? hi - lo : 0u;
-        if (MODE != 1 && hi) {                               // leave the table clear
+        lo = K_up - min(lo_down, K_up);
+        n = (lo_down != 0 && hi > lo && hi <= K_up) ? hi - lo : 0u;
+        if (MODE != 1 && (hi | lo_down)) {                   // leave the table clear
           tab_start[at] = 0;
           tab_end[at] = 0;
         }
