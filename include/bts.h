@@ -28,6 +28,13 @@
  *
  * Return value of every call: BTS_OK, or a negative code.  Arguments are checked
  * before anything is launched; on BTS_EINVAL nothing has been queued.
+ *
+ * What a context remembers between calls is scratch kept clean and, per direction, where
+ * the last call found its rows' thresholds: from its third compression on a context starts
+ * its search there instead of sampling the rows (a training run's threshold moves little
+ * from step to step).  That only decides how long a call takes, never what it returns:
+ * every output of every call is the exact Top_K defined above, whatever the history of the
+ * context.
  */
 #ifndef BTS_H
 #define BTS_H
