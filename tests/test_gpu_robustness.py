@@ -197,3 +197,34 @@ def test_bounds_handed_from_call_to_call_never_decide_the_result(oracle):
     assert paths[0] == (N, 0) and paths[1] == (N, 0) and paths[2] == (N, 0), paths
     assert any(p[1] > 0 for p in paths[3:7]), f"the jumps should have sent rows to the redo: {paths}"
     assert paths[8] == (N, 0) and paths[11] == (N, 0), f"bounds did not recover: {paths}"
+
+
+@pytest.mark.parametrize("K_dn", [500, 6000])
+def test_whole_step_with_rows_that_the_dense_path_redoes(oracle, K_dn):
+    """A whole step on the single-pass path in which some worker rows are handed to the dense
+    path (three magnitudes only: a third of the row ties at the top and the candidate lists
+    overflow) and the others finish in the single pass.  The select's last launch then fills
+    the aggregation's range tables both ways (from the finished messages; pair by pair for
+    the redone rows) and applies the downlink message to the model (K_dn = 6000: after the
+    emission; 500: by the emitting lanes); every output must be the oracle's, over several
+    steps with carried residuals."""
+    import _gpu_util as G
+    rng = np.random.default_rng(777 + K_dn)
+    N, d, K_up = 6, 400_003, 700
+    D = G.dev()
+    p = rng.dirichlet(np.ones(N)).astype(np.float32)
+    w0 = rng.standard_normal(d).astype(np.float32)
+    st = G.GpuState(N, d, K_up, K_dn, w0, p)
+    st.ctx.set_path(2)
+    saw_both = False
+    for step in range(5):
+        g = rng.standard_normal((N, d)).astype(np.float32)
+        tied = rng.integers(1, 4, size=(N // 2, d)).astype(np.float32)
+        g[::2] = tied * rng.choice(np.array([-1.0, 1.0], np.float32), size=tied.shape)
+        if step >= 3:
+            g[::2] *= 1e-3            # now the tied rows are small next to their residuals
+        st.step_and_compare(oracle, torch.from_numpy(g).to(D), 0.25, 1.0, f"step {step}")
+        fast, dense = st.ctx.last_path(0)
+        assert fast + dense == N
+        saw_both = saw_both or (fast > 0 and dense > 0)
+    assert saw_both, "no step mixed rows of both kinds"
