@@ -78,7 +78,7 @@ hipError_t dense_select(hipStream_t s, const DenseScratch& sc, const float* g, f
 
 // The pieces of dense_select for a caller that runs the first four kernels (three digit
 // histograms and the per-chunk counts, see dense_bodies.h) inside launches of its own:
-// dense_begin before them, dense_finish (scan of the counts and emission) after them.
+// dense_begin before them, dense_finish (the emission) after them.
 struct DensePlan {
   uint32_t nwc;        // wave chunks per row
   uint32_t gx;         // blocks in x of the looping kernels

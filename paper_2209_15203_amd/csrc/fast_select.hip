@@ -4,18 +4,23 @@
 // coordinate.  A radix select that histograms first and gathers afterwards reads the row
 // again; this path avoids the second read for typical inputs and stays exact:
 //
-//   1. sample:   a strided sample (256-coordinate slices, every S-th slice) of a = eps +
-//                alpha g is histogrammed on the top 13 bits of the magnitude key; a lower
-//                bound L is chosen so that between 1.15 K and 2 K coordinates of the row (by
-//                the sample's size) are expected at or above it.
-//   2. stream:   the one dense pass computes a, stores it over eps and appends every
-//                coordinate with key >= L to the row's candidate lists: the hits of a wave
-//                chunk (512 coordinates) go, in index order, into one run of one list (one
-//                atomic add per chunk with hits), and the chunk notes where its run starts
-//                and how long it is in the row's chunk directory.
+//   1. bounds:   on a scratch's first two calls a strided sample (256-coordinate slices,
+//                every S-th slice) of a = eps + alpha g is histogrammed on the top 13 bits of
+//                the magnitude key; a lower bound L is chosen so that between 1.15 K and 2 K
+//                coordinates of the row (by the sample's size) are expected at or above it,
+//                and a bound U near the K-th largest key.  Later calls take both from the
+//                exact threshold the call before found (cand_finish_body): no sample.
+//   2. stream:   the one dense pass computes a, stores it over eps (+0 instead where
+//                key >= U: those coordinates are almost surely sent, which spares the
+//                emission most of its scattered zero stores) and appends every coordinate
+//                with key >= L to the row's candidate lists: the hits of a wave chunk (512
+//                coordinates) go, in index order, into one run of one list (one atomic add
+//                per chunk with hits), and the chunk notes where its run starts and how long
+//                it is in the row's chunk directory.
 //   3. verify:   if no list overflowed and the lists hold at least K entries, the K largest
-//                of the row are all listed.  Otherwise the row is flagged and the dense path
-//                (which reads the stored a again) redoes it.  The result never depends on L.
+//                of the row are all listed.  Otherwise the row is flagged, gets back the
+//                values that step 2 replaced by +0, and the dense path (which reads the
+//                stored a again) redoes it.  The result never depends on L or U.
 //   4. select:   exact radix select of the K-th largest key T over the lists, on key - L in
 //                a 13-bit and a 12-bit digit, and r = how many holders of T are kept (a row
 //                whose T lies more than four octaves above L goes to the dense path too).
@@ -24,8 +29,10 @@
 //                tiles, then walk each tile again: an entry is kept if it is greater, or
 //                equal with fewer than r equal ones before it (lower index wins); its place
 //                in the message is #greater before + min(#equal before, r).  The pair comes
-//                from the list (no second read of eps), +0 is stored to eps there, and the
-//                directory entries are zeroed for the next call.
+//                from the list (no second read of eps), +0 is stored to eps there unless
+//                step 2 did (and the value goes back where step 2 zeroed a coordinate that
+//                is not sent after all), and the directory entries are zeroed for the next
+//                call.
 //
 // Steps 4-5 touch O(K) data.  Used for the worker compression (rows = N, fused with the
 // error compensation of Algorithm 2) and for the server compression (one row, no fusion).
@@ -48,7 +55,9 @@ constexpr int kSampleBins = 1 << kSampleBits;         // 8192
 constexpr int kSampleShift = 31 - kSampleBits;        // 18
 constexpr uint32_t kSlice = kWave * 4;                // 256 coordinates: one f4 per lane
 constexpr int kSliceUnroll = 8;
-constexpr uint32_t kMaxHistBlocks = 8;                // blocks per row in a candidate pass
+// blocks per row in a candidate pass (16 take 2 us off the first pass at 16 x 1.4e5 entries and
+// add 5 us to the two kernels that add their partial histograms up)
+constexpr uint32_t kMaxHistBlocks = 8;
 
 // ---- 1. sample histogram ------------------------------------------------------------
 // Slices are cut at absolute multiples of 256 coordinates (16-byte aligned); only slices
@@ -204,7 +213,7 @@ k_stream_capture(const float* __restrict__ g, float* __restrict__ x, uint64_t d,
 //                  largest of the row are all listed; else need = 1) and histograms d0.
 //   k_cand_hist1:  every block resolves d0 from the partial histograms, then histograms d1
 //                  of the entries in d0's bin.
-//   k_cand_finish: one block per row resolves d1: T and r.
+//   k_finish_hist0: one block per row resolves d1: T and r (cand_finish_body).
 //
 // A few fat blocks per row, each histogramming whole lists in LDS and storing its partial
 // histogram with plain stores: no cross-block atomics, no fences, nothing to clear.
@@ -505,9 +514,9 @@ __device__ __forceinline__ void cand_finish_body(uint32_t row,
 // scans the run lengths, then its lanes take the tile's entries round-robin in that order,
 // finding an entry's run by bisection on the scanned lengths.
 //
-//   k_dir_count: per tile, how many entries are greater than T and how many equal T.
-//   k_dir_scan:  per row, exclusive prefix of those pairs over the tiles.
-//   k_dir_emit:  per tile again: an entry is kept if it is greater, or equal with fewer
+//   dir_count_body: per tile, how many entries are greater than T and how many equal T.
+//   dir_scan_body:  per row, exclusive prefix of those pairs over the tiles.
+//   dir_emit_body:  per tile again: an entry is kept if it is greater, or equal with fewer
 //                than r equal ones before it (lower index wins); its place in the message
 //                is #greater before + min(#equal before, r).  Writes the pair, stores +0 to
 //                x there and zeroes the tile's directory entries (also for rows that the
@@ -682,8 +691,9 @@ __device__ __forceinline__ void dir_emit_body(
 // single-pass select and the first four of the dense redo of the flagged rows (idle unless
 // a row is flagged, but a launch costs 4-5 us either way) do not depend on each other, so
 // each pair shares a launch: the first `own` workgroups of the 1-D grid do the select's
-// part, the others the dense part on a virtual (gx, rows) grid.  The rest of the redo
-// (scan of the counts, emission) follows in launches of its own.
+// part, the others the dense part on a virtual (gx, rows) grid.  The redo's emission
+// follows in a launch of its own, whose workgroups, idle for rows that need no redo, fill
+// the aggregation's range tables or apply the model update from the finished messages.
 struct DensePart {
   float* x;
   uint64_t d;
