@@ -58,14 +58,11 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* l
   uint32_t inc = wave_inclusive_scan(v);
   if (l == kWave - 1) lds[w] = inc;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t acc = 0;
-    for (int i = 0; i < nw; ++i) {
-      uint32_t t = lds[i];
-      lds[i] = acc;
-      acc += t;
-    }
-    lds[nw] = acc;
+  if (w == 0) {                                   // the waves' sums, scanned by the first wave
+    const uint32_t t = l < nw ? lds[l] : 0u;      // (at most 16 of them)
+    const uint32_t s = wave_inclusive_scan(t);
+    if (l < nw) lds[l] = s - t;
+    if (l == nw - 1) lds[nw] = s;
   }
   __syncthreads();
   uint32_t res = inc - v + lds[w];
