@@ -216,36 +216,40 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
   const uint64_t below = lanes_below();
   uint32_t k_rem = K - bd.above;                   // >= 1: bin b holds the K-th largest key
   // the row's candidates, counted from the directory: thread t owns `per` consecutive chunks
+  // (their directory entries stay in registers for the gather below)
+  constexpr uint32_t kMaxPer = kMidMaxTiles * kTileChunks / kMidBlock;      // 16
   const uint32_t per = (nwc_pad + kMidBlock - 1) / kMidBlock;
   const uint32_t c0 = min(t * per, nwc_pad), c1 = min(c0 + per, nwc_pad);
+  uint2 ent[kMaxPer];
   uint32_t mine = 0;
-  for (uint32_t c = c0; c < c1; ++c) mine += dir_row[c].y;
+#pragma unroll
+  for (uint32_t u = 0; u < kMaxPer; ++u) {
+    ent[u] = c0 + u < c1 ? dir_row[c0 + u] : make_uint2(0u, 0u);
+    mine += ent[u].y;
+  }
   uint32_t total;
   uint32_t at = block_exclusive_scan(mine, lds, &total);
 
   if (total <= kLdsEntries) {
     // ---- the candidates fit in LDS: gather them in index order, do the rest there ----------
     uint2* s_ent = reinterpret_cast<uint2*>(pool);
-    // four chunks at a time: their directory entries, then the first entry of each run (most
-    // runs hold one entry where K is a thousandth of d), loaded together; longer runs after
-    for (uint32_t cb = c0; cb < c1; cb += 4) {
-      uint2 ent[4], first[4];
+    // the first entry of each of the thread's runs (most runs hold one entry where K is a
+    // thousandth of d), loaded together; longer runs after
+    {
+      uint2 first[kMaxPer];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        ent[u] = cb + u < c1 ? dir_row[cb + u] : make_uint2(0u, 0u);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (uint32_t u = 0; u < kMaxPer; ++u) {
         first[u] = make_uint2(0u, 0u);
         if (ent[u].y) {
-          dir_row[cb + u] = make_uint2(0u, 0u);    // leave the directory clear
-          first[u] = cand_row[(uint64_t)((cb + u) % kSubLists) * cap + ent[u].x];
+          dir_row[c0 + u] = make_uint2(0u, 0u);    // leave the directory clear
+          first[u] = cand_row[(uint64_t)((c0 + u) % kSubLists) * cap + ent[u].x];
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (uint32_t u = 0; u < kMaxPer; ++u) {
         if (ent[u].y == 0) continue;
         if (at < kLdsEntries) s_ent[at] = first[u];
-        const uint2* run = cand_row + (uint64_t)((cb + u) % kSubLists) * cap + ent[u].x;
+        const uint2* run = cand_row + (uint64_t)((c0 + u) % kSubLists) * cap + ent[u].x;
         for (uint32_t j = 1; j < ent[u].y; ++j)
           if (at + j < kLdsEntries) s_ent[at + j] = run[j];
         at += ent[u].y;
@@ -277,7 +281,18 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
     // 4 bytes at pos <= e against 8 at e), for the range table below.
     uint32_t* s_idx = pool;
     uint32_t run_gt = 0, run_eq = 0;
-    for (uint32_t e0 = 0; e0 < total; e0 += kMidBlock) {
+    // the model update of the pairs this thread emits: their loads of w go out together after
+    // the loop (a load per turn of the loop would be waited for in every turn)
+    constexpr uint32_t kEmitTurns = kLdsEntries / kMidBlock;
+    static_assert(kEmitTurns * kMidBlock == kLdsEntries, "whole turns");
+    uint32_t upd_i[kEmitTurns];
+    float upd_v[kEmitTurns];
+#pragma unroll
+    for (uint32_t turn = 0; turn < kEmitTurns; ++turn) {
+      upd_i[turn] = 0xFFFFFFFFu;
+      upd_v[turn] = 0.0f;
+      const uint32_t e0 = turn * kMidBlock;
+      if (e0 >= total) continue;                   // the same for every thread
       const uint32_t e = e0 + t;
       const uint2 en = e < total ? s_ent[e] : make_uint2(0u, 0u);
       const uint32_t key = en.y & 0x7FFFFFFFu;
@@ -306,12 +321,23 @@ __global__ __launch_bounds__(kMidBlock) void k_mid_finish(
           oi[pos] = en.x;
           ov[pos] = val;
           xr[en.x] = 0.0f;
-          if (upd.w != nullptr) upd.w[en.x] = __fmaf_rn(upd.neg_alpha, val, upd.w[en.x]);
+          upd_i[turn] = en.x;
+          upd_v[turn] = val;
         }
       }
       run_gt += all_gt;
       run_eq += all_eq;
       __syncthreads();
+    }
+    if (upd.w != nullptr) {
+      float wv[kEmitTurns];
+#pragma unroll
+      for (uint32_t turn = 0; turn < kEmitTurns; ++turn)
+        wv[turn] = upd_i[turn] != 0xFFFFFFFFu ? upd.w[upd_i[turn]] : 0.0f;
+#pragma unroll
+      for (uint32_t turn = 0; turn < kEmitTurns; ++turn)
+        if (upd_i[turn] != 0xFFFFFFFFu)
+          upd.w[upd_i[turn]] = __fmaf_rn(upd.neg_alpha, upd_v[turn], wv[turn]);
     }
   } else {
     // ---- long lists (a crowded threshold bin): the same steps from the lists in memory -----
