@@ -74,3 +74,36 @@ def test_random_case(oracle, seed):
             g = np.where(np.isinf(g), np.float32(3e38), g).astype(np.float32) if t == 1 else g
         st.step_and_compare(oracle, torch.from_numpy(g).to(G.dev()), alpha, a_out,
                             f"{tag} step {t}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_case_over_several_steps(oracle, seed):
+    """Five steps on one context with the kind of gradient changing from step to step, on
+    shapes the single-pass select serves: from its third call on that select starts from the
+    bounds of the call before, which here belong to another distribution every time (lists
+    that overflow or fall short, early zeros to take back, rows redone by the dense path and
+    picked up again).  Every output of every step bit for bit against the oracle."""
+    import _gpu_util as G
+    rng = np.random.default_rng(5000 + seed)
+    N = int(rng.integers(1, 9))
+    d = int(np.exp(rng.uniform(np.log(66_000), np.log(500_000))))
+    K_up = int(rng.integers(1, d // 64 + 1))
+    K_dn = int(rng.integers(1, d // 64 + 1)) if seed % 3 else int(rng.integers(1, d + 1))
+    path = 2 if seed % 4 else 0
+    alpha = float(rng.choice([1.0, 0.5, 0.01, 0.37]))
+    a_out = float(rng.choice([1.0, 0.3]))
+    p = rng.dirichlet(np.ones(N)).astype(np.float32)
+    w0 = rng.standard_normal(d).astype(np.float32)
+    st = G.GpuState(N, d, K_up, K_dn, w0, p)
+    st.ctx.set_path(path)
+    tag = f"seed {seed}: N={N} d={d} K_up={K_up} K_dn={K_dn} path={path}"
+    same_kind = seed % 2 == 0                    # half the cases keep one distribution
+    for t in range(5):
+        kind = KINDS[seed % len(KINDS)] if same_kind else KINDS[(seed + 3 * t) % len(KINDS)]
+        g = draw_rows(rng, kind, N, d)
+        if t > 0:                                # inf - inf would make NaN (payload not compared)
+            g = np.where(np.isinf(g), np.float32(3e38), g).astype(np.float32)
+        if same_kind and kind == "normal":
+            g *= np.float32(1.0 + 0.2 * t)       # a drifting scale
+        st.step_and_compare(oracle, torch.from_numpy(g).to(G.dev()), alpha, a_out,
+                            f"{tag} step {t} ({kind})")
