@@ -211,12 +211,17 @@ k_stream_capture(const float* __restrict__ g, float* __restrict__ x, uint64_t d,
 //
 //   k_cand_hist0:  verifies the row (no list overflowed, at least K entries: then the K
 //                  largest of the row are all listed; else need = 1) and histograms d0.
-//   k_cand_hist1:  every block resolves d0 from the partial histograms, then histograms d1
-//                  of the entries in d0's bin.
-//   k_finish_hist0: one block per row resolves d1: T and r (cand_finish_body).
+//   k_cand_hist1:  every block resolves d0 from the partial histograms (and, in the same
+//                  steps, the bin of the entry at the rank the next call's bound aims at),
+//                  then histograms d1 of the entries in d0's bin.
+//   k_finish_hist0: one block per row resolves d1: T and r (cand_finish_body), and leaves
+//                  the next call's bounds.
 //
-// A few fat blocks per row, each histogramming whole lists in LDS and storing its partial
-// histogram with plain stores: no cross-block atomics, no fences, nothing to clear.
+// A few fat blocks per row, each histogramming its share of the lists in LDS.  The d0
+// histograms are stored per block with plain stores (no cross-block atomics, no fences,
+// nothing to clear) and added up by the blocks of the next kernel, coarse sums first; the d1
+// histogram, which has a few hundred entries at most unless the threshold is a much-repeated
+// value, is added to one histogram of the row, which the finishing block zeroes again.
 constexpr int kD1Bits = 12;
 constexpr int kD0Bins = 8192, kD1Bins = 1 << kD1Bits;
 constexpr int kD0Coarse = 256;                        // sums over 32 consecutive d0 bins
@@ -444,8 +449,15 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
     }
   }
   __syncthreads();
-  uint32_t* out = part_row + (uint64_t)blockIdx.x * kPartWords + kD0Bins;
-  for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) out[i] = sh[i];
+  // The threshold's bin holds few entries (a few hundred of a row's hundred thousand
+  // candidates), so the blocks add their few non-zero counts to ONE histogram of the row (the
+  // d1 part of the row's first partial, zero between calls) instead of storing 4096 words each
+  // for the next kernel to add up.
+  uint32_t* out = part_row + kD0Bins;
+  for (int i = threadIdx.x; i < kD1Bins; i += kCandBlock) {
+    const uint32_t v = sh[i];
+    if (v) atomicAdd(&out[i], v);
+  }
 }
 
 // Also sets the row's bounds for the NEXT call on this scratch, which then needs no sample:
@@ -460,7 +472,7 @@ __global__ __launch_bounds__(kCandBlock) void k_cand_hist1(const uint2* __restri
 // lists fall short or overflow to the dense path, whose emission sets the row's bounds from
 // its exact threshold instead (k_emit).
 __device__ __forceinline__ void cand_finish_body(uint32_t row,
-                                                 const uint32_t* __restrict__ partial,
+                                                 uint32_t* __restrict__ partial,
                                                  uint32_t nparts, bool early_zero,
                                                  uint32_t* __restrict__ lower_key,
                                                  uint32_t* __restrict__ upper_key,
@@ -475,10 +487,11 @@ __device__ __forceinline__ void cand_finish_body(uint32_t row,
     cand_cnt[((uint64_t)row * kSubLists + threadIdx.x) * kCounterStride] = 0;
   if (need[row]) return;
   const FastSel s = sel[row];
-  const uint32_t* part_row = partial + (uint64_t)row * nparts * kPartWords;
+  uint32_t* d1 = partial + (uint64_t)row * nparts * kPartWords + kD0Bins;   // the row's one d1 histogram
   uint32_t above;
-  const uint32_t b1 = resolve_bins<kD1Bins, kBlock>(part_row + kD0Bins, nparts, kPartWords,
-                                                    s.k_rem, lds, s_out, &above);
+  const uint32_t b1 = resolve_bins<kD1Bins, kBlock>(d1, 1, 0, s.k_rem, lds, s_out, &above);
+  for (int i = threadIdx.x; i < kD1Bins; i += kBlock)     // zero again for the next call
+    if (d1[i]) d1[i] = 0;
   if (threadIdx.x == 0) {
     const uint32_t b_next = s.next_bin;    // first-digit bin of the entry at rank rank_next
     const uint32_t L = lower_key[row];
@@ -710,7 +723,7 @@ __device__ __forceinline__ VGrid dense_vgrid(uint32_t b, const DensePart& dp) {
   return VGrid{b % dp.gx, b / dp.gx, dp.gx};
 }
 
-__global__ __launch_bounds__(kBlock) void k_finish_hist0(uint32_t own, const uint32_t* partial,
+__global__ __launch_bounds__(kBlock) void k_finish_hist0(uint32_t own, uint32_t* partial,
                                                          uint32_t nparts, bool early_zero,
                                                          uint32_t* lower_key,
                                                          uint32_t* upper_key, uint32_t* prev_T,
@@ -852,6 +865,7 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                             (uint64_t)sc.rows * pl.nwc_pad * 2, 0);
     if (e == hipSuccess) e = fill_u32(s, sc.sample_hist, (uint64_t)sc.rows * kSampleBins, 0);
     if (e == hipSuccess) e = fill_u32(s, sc.prev_T, sc.rows, 0);
+    if (e == hipSuccess) e = fill_u32(s, sc.hist, (uint64_t)sc.rows * fast_hist_words(), 0);
     if (e != hipSuccess) return e;
   }
   // 1. bounds: from a sample on the scratch's first two calls and after a failed one; later
