@@ -1,8 +1,9 @@
 """GPU parity on the paper's own workload shapes (experiments section): model sizes
 d in {29,034; 50,890; 242,762; 1,199,882; 20,040,522}, N in {20, 50, 100} workers,
 K = d - floor(0.999 d) both ways, p_q = 1/N (not a power of two, so a fused and an
-unfused multiply-add differ).  Synthetic gradients stand in for the training runs; two
-steps with carried residuals, every output bit for bit against the oracle.
+unfused multiply-add differ).  Synthetic gradients stand in for the training runs; four
+steps with carried residuals (from the third on the single-pass select starts from the
+bounds of the step before), every output bit for bit against the oracle.
 
 Also the appendix toy example (N = 3, d = 100, K = 1, closed-form gradients that depend
 on w) stepped through the GPU library for 300 iterations in both the bidirectional and the
@@ -32,11 +33,11 @@ def shapes():
 def test_paper_shape(oracle, N, d):
     import _gpu_util as G
     K = wl.k_from_fraction(d, 1, 1000)
-    cfg = wl.Config(f"paper-d{d}-N{N}", 100 + N, N, d, K, K, 2, "normal")
+    cfg = wl.Config(f"paper-d{d}-N{N}", 100 + N, N, d, K, K, 4, "normal")
     src = wl.GradientSource(cfg, G.dev())
     p = np.full(N, 1.0 / N, np.float32)
     st = G.GpuState(N, d, K, K, wl.weights0(cfg, "cpu").numpy(), p)
-    for t in (1, 2):
+    for t in (1, 2, 3, 4):
         st.step_and_compare(oracle, src.step(t), 0.05, 1.0, f"{cfg.name} step {t}")
 
 
