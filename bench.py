@@ -87,13 +87,14 @@ def cpu_baseline(cfg, g_first, threads):
 
 
 def source_digest() -> str:
-    """Digest of the kernel sources a recorded counter reading belongs to."""
-    import glob
+    """Digest of the sources of the dominant kernel (the single-pass select and what it
+    includes), which a recorded counter reading belongs to."""
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2209_15203_amd", "csrc", "*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in ("bts_device.h", "bts_internal.h", "capture_bodies.h", "dense_bodies.h",
+                 "fast_select.hip"):
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2209_15203_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 
 

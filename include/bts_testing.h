@@ -42,6 +42,18 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
  * Results are identical in every mode. */
 int bts_set_path(bts_ctx* ctx, int mode);
 
+/* Testing aid, no device needed: how a select of `rows` rows of d coordinates with K kept
+ * coordinates is planned.  out (host pointer, 16 words): [0] the path that serves the shape
+ * by default (0 one workgroup per row, 1 dense multi-pass, 2 single-pass, 3 three-launch);
+ * single-pass select: [1] possible for the shape, [2] capacity of one candidate list,
+ * [3] sample stride in slices, [4] sampled coordinates wanted at or above the lower bound,
+ * [5] the rank the handed-on lower bound aims at, [6] directory tiles per row, [7] directory
+ * entries per row, [8] waves per SIMD the dense pass is held to; three-launch select:
+ * [9] possible for the shape, [10] capacity of one list, [11] tiles, [12] directory entries
+ * per row, [13] blocks per row of the capture, [14] of the histogram pass; [15] candidate
+ * lists per row.  BTS_EINVAL for rows == 0, d == 0, d >= 2^32, K > d or a null pointer. */
+int bts_testing_plan(uint32_t rows, uint64_t d, uint32_t K, uint32_t* out);
+
 /* Testing aid: makes the next calls on this context behave as after a call that failed
  * half way (a HIP launch error): the select scratch is taken to be dirty, so the next
  * select clears its histograms, directory and sample counts before it starts, and the

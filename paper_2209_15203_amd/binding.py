@@ -16,7 +16,7 @@ EXPORTS = ["bts_create", "bts_destroy", "bts_last_hip_error", "topk_compress",
            "unidir_step", "bts_enable_diagnostics", "bidir_step_diag"]
 # testing and measurement aids of the same library (include/bts_testing.h)
 TESTING_EXPORTS = ["bts_profile_enable", "bts_profile_read", "bts_last_path", "bts_set_path",
-                   "bts_testing_mark_dirty"]
+                   "bts_testing_mark_dirty", "bts_testing_plan"]
 # the measurement instrument, a library of its own (include/bts_probe.h)
 PROBE_EXPORTS = ["bts_hbm_probe"]
 _PROBE_PATH = os.path.join(_HERE, "libbts_probe.so")
@@ -62,11 +62,27 @@ def load_library():
     lib.bts_last_path.argtypes = [vp, C.c_int, C.POINTER(u32), C.POINTER(u32)]
     lib.bts_set_path.argtypes = [vp, C.c_int]
     lib.bts_testing_mark_dirty.argtypes = [vp]
+    lib.bts_testing_plan.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.POINTER(C.c_uint32)]
     for name in EXPORTS + TESTING_EXPORTS:
         if name != "bts_destroy":
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
+
+
+PLAN_FIELDS = ("path", "single_pass_possible", "list_cap", "sample_stride", "sample_target",
+               "rank_next", "tiles", "dir_entries", "waves_per_simd", "three_launch_possible",
+               "three_launch_cap", "three_launch_tiles", "three_launch_dir_entries",
+               "three_launch_blocks", "three_launch_hist_blocks", "lists")
+
+
+def testing_plan(rows: int, d: int, K: int) -> dict:
+    """How the library plans a select of this shape (host logic only: needs no GPU)."""
+    out = (C.c_uint32 * 16)()
+    rc = load_library().bts_testing_plan(rows, d, K, out)
+    if rc != 0:
+        raise BtsError(f"bts_testing_plan failed: {rc}")
+    return dict(zip(PLAN_FIELDS, list(out)))
 
 
 def load_probe_library():

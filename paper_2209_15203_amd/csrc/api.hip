@@ -546,6 +546,33 @@ int bts_last_path(bts_ctx* ctx, int which, uint32_t* rows_fast, uint32_t* rows_d
   return BTS_OK;
 }
 
+int bts_testing_plan(uint32_t rows, uint64_t d, uint32_t K, uint32_t* out) {
+  if (out == nullptr || rows == 0 || d == 0 || d >= (1ull << 32) || K > d) return BTS_EINVAL;
+  const FastPlan fp = fast_plan(rows, d, K);
+  const MidPlan mp = mid_plan(rows, d, K);
+  uint32_t path = 1;                                          // dense multi-pass
+  if (K != 0 && row_select_fits(d)) path = 0;                 // one workgroup per row
+  else if (K != 0 && mp.enabled && mp.preferred) path = 3;    // three launches
+  else if (K != 0 && fp.enabled && fp.preferred) path = 2;    // single pass
+  out[0] = path;
+  out[1] = fp.enabled ? 1u : 0u;
+  out[2] = fp.cap;
+  out[3] = fp.stride;
+  out[4] = fp.target;
+  out[5] = fp.rank_next;
+  out[6] = fp.ntiles;
+  out[7] = fp.nwc_pad;
+  out[8] = fp.stream_waves_per_simd;
+  out[9] = mp.enabled ? 1u : 0u;
+  out[10] = mp.cap;
+  out[11] = mp.ntiles;
+  out[12] = mp.nwc_pad;
+  out[13] = mp.gx;
+  out[14] = mp.gx_hist;
+  out[15] = fast_sublists();
+  return BTS_OK;
+}
+
 int bts_testing_mark_dirty(bts_ctx* ctx) {
   if (!ctx) return BTS_EINVAL;
   ctx->dense_dirty = true;
