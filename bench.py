@@ -226,7 +226,10 @@ def main() -> int:
 
     total = torch.cuda.get_device_properties(dev).total_memory
     batch_bytes = 4 * N * d
-    want = args.buffers if args.buffers > 0 else args.steps + args.warmup
+    # a fresh batch for every call of the run where memory allows: warm-up, timed steps and the
+    # steps of the dominant kernel's timing loop (a batch that comes round again adds to the
+    # residuals it left behind, which is not what a training run's next gradient does)
+    want = args.buffers if args.buffers > 0 else 2 * args.steps + args.warmup
     fit = max(1, int((total * 0.80 - 1.2 * batch_bytes) // batch_bytes))
     n_buf = max(1, min(want, fit))
 
