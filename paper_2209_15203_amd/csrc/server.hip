@@ -22,7 +22,7 @@ namespace {
 constexpr int kAggBlock = 256;
 constexpr int kAggWaves = kAggBlock / kWave;
 constexpr uint32_t kAggStage = 256;    // pairs a wave holds in registers at a time (4 per lane)
-constexpr uint32_t kAggMaxBlocks = 2048;
+constexpr uint32_t kAggMaxBlocks = 8192;
 
 __device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t* __restrict__ a, uint32_t n,
                                                     uint32_t key) {
@@ -416,8 +416,15 @@ __global__ void k_update(const uint32_t* __restrict__ idx, const float* __restri
 uint32_t aggregate_ranges(uint64_t d) { return (uint32_t)((d + kAggWidth - 1) / kAggWidth); }
 
 namespace {
+// About four ranges to three waves: a wave with a second range fetches its table entries
+// while it works on the first, and more waves than that leave each with no second range
+// (measured per launch at 10.9 / 25 / 107 thousand ranges: 30.7 / 52 / 25 us, against
+// 34 / 55 / 28 us with a wave per range or with three ranges per wave).
+// (Up to the 6144 waves the chip holds at once, a wave per range: 5.8 against 8.2 us at 1024.)
 uint32_t agg_blocks(uint32_t ranges) {
-  uint32_t b = (ranges + kAggWaves - 1) / kAggWaves;
+  uint32_t b = ranges <= 6144u ? (ranges + kAggWaves - 1) / kAggWaves
+                               : (uint32_t)(((uint64_t)ranges * 3 + 15) / 16);
+  if (b < 1) b = 1;
   return b > kAggMaxBlocks ? kAggMaxBlocks : b;
 }
 }  // namespace
