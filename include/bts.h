@@ -32,7 +32,8 @@
  * What a context remembers between calls is scratch kept clean and, per direction, where
  * the last call found its rows' thresholds: from its third compression on a context starts
  * its search there instead of sampling the rows (a training run's threshold moves little
- * from step to step).  That only decides how long a call takes, never what it returns:
+ * from step to step; after a call in which that start proved useless it samples again for a
+ * few calls).  That only decides how long a call takes, never what it returns:
  * every output of every call is the exact Top_K defined above, whatever the history of the
  * context.
  */

@@ -21,7 +21,7 @@ struct bts_ctx {
   DenseScratch dense;
   bool dense_dirty;
   bool fast_up_dirty, fast_dn_dirty;
-  uint32_t fast_up_calls, fast_dn_calls, fast_diag_u_calls, fast_diag_v_calls;
+  FastScratch::HostState fast_up_host, fast_dn_host, fast_diag_u_host, fast_diag_v_host;
   FastPlan plan_up, plan_dn;
   FastScratch fast_up, fast_dn;
   MidPlan mid_plan_up, mid_plan_dn;   // the three-launch select of middling rows with small K
@@ -40,6 +40,7 @@ struct bts_ctx {
   DiagScratch diag;             // allocated by bts_enable_diagnostics only
   bool diag_ready;
   std::vector<void*> owned;     // every device allocation of the context
+  std::vector<void*> owned_host;   // every pinned host allocation of the context
   // timing of the dominant kernel
   bool profile;
   int path_mode;                // 0 = by shape, 1 = dense only, 2 = single-pass where possible,
@@ -102,6 +103,21 @@ bool alloc_fast(bts_ctx* ctx, const FastPlan& pl, uint32_t rows, FastScratch* sc
   sc->sel = sel;
   sc->tile_cnt = sup;
   sc->rows = rows;
+  // the pinned word through which a redo is reported to the host (see fast_select)
+  sc->redone_host = nullptr;
+  sc->redone_dev = nullptr;
+  void* pinned = nullptr;
+  if (ok && hipHostMalloc(&pinned, 64, hipHostMallocMapped) == hipSuccess) {
+    ctx->owned_host.push_back(pinned);
+    void* dev_ptr = nullptr;
+    if (hipHostGetDevicePointer(&dev_ptr, pinned, 0) == hipSuccess) {
+      *static_cast<volatile uint32_t*>(pinned) = 0;
+      sc->redone_host = static_cast<volatile uint32_t*>(pinned);
+      sc->redone_dev = static_cast<uint32_t*>(dev_ptr);
+    }
+  } else if (ok) {
+    (void)hipGetLastError();          // without the word a redo is simply never reported
+  }
   return ok;
 }
 
@@ -129,6 +145,7 @@ bool alloc_agg_tables(bts_ctx* ctx) {
 
 void release(bts_ctx* ctx) {
   for (void* q : ctx->owned) (void)hipFree(q);
+  for (void* q : ctx->owned_host) (void)hipHostFree(q);
   for (auto& pr : ctx->ev_pool) {
     (void)hipEventDestroy(pr.first);
     (void)hipEventDestroy(pr.second);
@@ -288,8 +305,8 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   ctx->dense_dirty = false;
   ctx->fast_up_dirty = ctx->fast_dn_dirty = ctx->fast_diag_u_dirty = false;
   ctx->fast_diag_v_dirty = false;
-  ctx->fast_up_calls = ctx->fast_dn_calls = ctx->fast_diag_u_calls = 0;
-  ctx->fast_diag_v_calls = 0;
+  ctx->fast_up_host = ctx->fast_dn_host = FastScratch::HostState{0, 0, 0, 0};
+  ctx->fast_diag_u_host = ctx->fast_diag_v_host = FastScratch::HostState{0, 0, 0, 0};
   ctx->fast_up = FastScratch{};
   ctx->fast_dn = FastScratch{};
   ctx->fast_diag_u = FastScratch{};
@@ -333,8 +350,8 @@ int bts_create(bts_ctx** out, int32_t N, uint64_t d, uint32_t K_up, uint32_t K_d
   // serves the shape alone.
   ctx->fast_up.dirty = &ctx->fast_up_dirty;
   ctx->fast_dn.dirty = &ctx->fast_dn_dirty;
-  ctx->fast_up.calls = &ctx->fast_up_calls;
-  ctx->fast_dn.calls = &ctx->fast_dn_calls;
+  ctx->fast_up.host = &ctx->fast_up_host;
+  ctx->fast_dn.host = &ctx->fast_dn_host;
   if (!alloc_fast(ctx, ctx->plan_up, rows, &ctx->fast_up)) {
     (void)hipGetLastError();
     ctx->plan_up.enabled = false;
@@ -446,13 +463,13 @@ int bts_enable_diagnostics(bts_ctx* ctx) {
   if (ok) {                            // the one-row select with K_up (falls back to dense)
     ctx->plan_diag_u = fast_plan(1, ctx->d, ctx->K_up);
     ctx->fast_diag_u.dirty = &ctx->fast_diag_u_dirty;
-    ctx->fast_diag_u.calls = &ctx->fast_diag_u_calls;
+    ctx->fast_diag_u.host = &ctx->fast_diag_u_host;
     if (!alloc_fast(ctx, ctx->plan_diag_u, 1, &ctx->fast_diag_u)) {
       (void)hipGetLastError();
       ctx->plan_diag_u.enabled = false;
     }
     ctx->fast_diag_v.dirty = &ctx->fast_diag_v_dirty;
-    ctx->fast_diag_v.calls = &ctx->fast_diag_v_calls;
+    ctx->fast_diag_v.host = &ctx->fast_diag_v_host;
     ok = alloc_fast(ctx, ctx->plan_dn, 1, &ctx->fast_diag_v);
   }
   if (ok && ctx->plan_up.enabled)      // partial sums of the rows' residual energies

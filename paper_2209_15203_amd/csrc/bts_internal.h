@@ -93,11 +93,12 @@ struct NextBounds {
   uint32_t* upper_key;     // written only if early_zero
   uint32_t* prev_T;
   bool early_zero;
+  uint32_t* redone;        // pinned host word (device address): set to 1 when a row is redone
 };
 hipError_t dense_finish(hipStream_t s, const DenseScratch& sc, const DensePlan& pl, float* x,
                         uint32_t rows, uint64_t d, uint32_t K, uint32_t* out_idx,
                         float* out_val, RowMask need, FusedUpdate upd,
-                        NextBounds heal = NextBounds{nullptr, nullptr, nullptr, false},
+                        NextBounds heal = NextBounds{nullptr, nullptr, nullptr, false, nullptr},
                         MidRanges ranges = MidRanges{nullptr, nullptr, nullptr});
 // (upd.after: rows that need no redo are updated from their finished message instead;
 // ranges, with a row mask only: the emission's launch also fills the range tables, for the
@@ -142,7 +143,18 @@ struct FastScratch {
                            // of its run in its list and the run's length
   void* tile_cnt;          // rows x ntiles 64-bit words (rewritten by every call)
   bool* dirty;             // host flag: a call failed half way, clear directory and sample first
-  uint32_t* calls;         // host counter: calls since the bounds were last sampled from scratch
+  // host side of the bounds handed from call to call
+  struct HostState {
+    uint32_t calls;        // calls since the bounds were last sampled from scratch
+    uint32_t cold_left;    // calls that still have to sample (after rows were redone)
+    uint32_t backoff;      // how many calls sampled after the last redo (doubles, up to 64)
+    uint32_t quiet;        // calls since a redo was last seen
+  };
+  HostState* host;
+  // pinned host word that the redo's emission sets when it redoes a row: the host looks at it,
+  // without waiting for anything, at the start of a later call (redone_dev: its device address)
+  volatile uint32_t* redone_host;
+  uint32_t* redone_dev;
   uint32_t rows;           // rows the scratch was sized for
   // diagnostics only (null otherwise): fp64 sums of squares of what stays behind in the row,
   // per wave chunk (coordinates not captured) and per directory tile (captured, not kept)

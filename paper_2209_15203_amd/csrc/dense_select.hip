@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kBlock) void k_emit(float* __restrict__ x, uint64_t
     heal.lower_key[row] = plain ? __float_as_uint(__uint_as_float(T) * 0.9f) : 0u;
     if (heal.early_zero) heal.upper_key[row] = T ? T : 0xFFFFFFFFu;
     heal.prev_T[row] = 0;                          // no trend across a redo
+    if (heal.redone != nullptr) *heal.redone = 1u; // the host samples again on a later call
   }
   const VGrid vg{blockIdx.x, blockIdx.y, gridDim.x};
   const ChunkShare sh = block_share(vg, nwc);

@@ -870,8 +870,24 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
   }
   // 1. bounds: from a sample on the scratch's first two calls and after a failed one; later
   // calls start from the bounds the call before them left (see cand_finish_body)
-  if (*sc.dirty) *sc.calls = 0;
-  const bool sampled = *sc.calls < 2;
+  // A row that was redone says so in a pinned host word; the host sees it on a later call (it
+  // never waits for it) and samples again for a while: 2 calls, and twice as many after every
+  // further redo, up to 64, so that a workload whose threshold cannot be foreseen (the same
+  // gradient fed again and again makes it grow by a half, a third, ... per step) ends up
+  // sampling almost always, as cheaply as if nothing were handed on; 64 calls without a redo
+  // forget the past.
+  FastScratch::HostState& hs = *sc.host;
+  if (*sc.dirty) hs = FastScratch::HostState{0, 0, 0, 0};
+  if (sc.redone_host != nullptr && *sc.redone_host != 0) {
+    *sc.redone_host = 0;
+    hs.backoff = hs.backoff == 0 ? 2u : (hs.backoff < 64u ? hs.backoff * 2u : 64u);
+    hs.cold_left = hs.backoff;
+    hs.quiet = 0;
+  } else if (++hs.quiet >= 64u) {
+    hs.backoff = 0;
+  }
+  const bool sampled = hs.calls < 2 || hs.cold_left > 0;
+  if (hs.cold_left > 0) --hs.cold_left;
   *sc.dirty = true;      // cleared when every launch of this call went out
   if (sampled) {
     const uint64_t n_samp = (d / 256) / pl.stride + 1;
@@ -976,10 +992,12 @@ hipError_t fast_select(hipStream_t s, const FastScratch& sc, const FastPlan& pl,
                                                     tile_energy, emit_upd, dp);
   BTS_LAUNCH_CHECK();
   *sc.dirty = false;
-  *sc.calls += 1;
+  hs.calls += 1;
   // the rest of the redo: emission of the flagged rows, which also sets their next bounds
   return dense_finish(s, dense, dpl, x, rows, d, K, out_idx, out_val, sc.need, upd,
-                      NextBounds{sc.lower_key, sc.upper_key, sc.prev_T, g != nullptr}, ranges);
+                      NextBounds{sc.lower_key, sc.upper_key, sc.prev_T, g != nullptr,
+                                 sc.redone_dev},
+                      ranges);
 }
 
 size_t fast_sel_bytes() { return sizeof(FastSel); }

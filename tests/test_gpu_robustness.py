@@ -228,3 +228,35 @@ def test_whole_step_with_rows_that_the_dense_path_redoes(oracle, K_dn):
         assert fast + dense == N
         saw_both = saw_both or (fast > 0 and dense > 0)
     assert saw_both, "no step mixed rows of both kinds"
+
+
+def test_the_same_gradient_fed_again_and_again(oracle):
+    """A caller that times the step in a loop over ONE gradient tensor: the residuals then grow
+    coherently and the thresholds by a half, a third, a quarter ... per step, faster than the
+    bounds handed from call to call follow at first.  The rows that are redone report it to the
+    host, which samples again for a few calls; after that the trend is slow enough to follow.
+    Every call exact; only a call or two may have rows redone."""
+    import _gpu_util as G
+    import paper_2209_15203_amd as bts
+    rng = np.random.default_rng(2024)
+    N, d, K = 4, 300_007, 600
+    D = G.dev()
+    ctx = bts.BtsContext(N, d, K, K)
+    ctx.set_path(2)
+    g = rng.standard_normal((N, d)).astype(np.float32)
+    tg = torch.from_numpy(g).to(D)
+    eps = np.zeros((N, d), np.float32)
+    te = torch.from_numpy(eps).to(D)
+    ui = torch.zeros((N, K), dtype=torch.int32, device=D)
+    uv = torch.zeros((N, K), dtype=torch.float32, device=D)
+    redone = []
+    for step in range(14):
+        bts.topk_compress(ctx, tg, te, 0.5, ui, uv)
+        torch.cuda.synchronize()
+        wi, wv = oracle.worker_stage(g, eps, 0.5, K)
+        G.assert_same_bits(ui, wi, f"step {step} up_idx")
+        G.assert_same_bits(uv, wv, f"step {step} up_val")
+        G.assert_same_bits(te, eps, f"step {step} eps")
+        redone.append(ctx.last_path(0)[1])
+    assert sum(1 for r in redone if r) <= 3, f"rows kept being redone: {redone}"
+    assert redone[-4:] == [0, 0, 0, 0], f"the select did not settle: {redone}"
