@@ -156,6 +156,34 @@ def record_traffic(cfg_name, fetch_csv, write_csv) -> int:
     return 0
 
 
+def probe_distance(N, d, dev, total_mem, repeats) -> int:
+    """The plain fma-stream (dst = fma(0.5, src, dst): the worker stage's 2 reads : 1 write,
+    held to 12 waves per compute unit like the library's dominant kernel) over two N x d
+    arrays of N(0, 1e-3) values inside one allocation, for a range of distances between
+    them.  One JSON line."""
+    import torch
+    from paper_2209_15203_amd import binding
+    GiB = 1 << 30
+    n = N * d // 512 * 512
+    span = int(total_mem * 0.80) // GiB * GiB
+    big = torch.empty(span // 4, dtype=torch.float32, device=dev)
+    piece = 1 << 28
+    for a in range(0, big.numel(), piece):
+        big[a:a + piece].normal_().mul_(1e-3)
+    torch.cuda.synchronize()
+    first = (4 * n + GiB - 1) // GiB * GiB                   # the arrays must not overlap
+    out = {"probe": "fma-stream over two arrays of one allocation against their distance",
+           "floats_per_array": n, "allocation_bytes": span, "by_distance_GiB": {}}
+    dist = first
+    while dist + 4 * n <= span:
+        ms = binding.hbm_probe(2, big[:n], big[dist // 4:dist // 4 + n], 12, True, repeats=repeats)
+        out["by_distance_GiB"][str(dist // GiB)] = {"ms": round(ms, 3),
+                                                    "frac_of_peak": round(12 * n / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        dist += 4 * GiB
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,6 +200,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain copy kernel of known size (2^28 floats read, 2^28 "
                          "written) so that a counter profile of this command can be scaled")
+    ap.add_argument("--probe-distance", action="store_true",
+                    help="no step: time the plain 2-reads-1-write stream over two N x d arrays "
+                         "carved from one allocation, against the distance between them")
     ap.add_argument("--probe-hbm", action="store_true",
                     help="instead of the step: time plain read / copy / fma-stream kernels with "
                          "the dominant kernel's access shape over the workload's g and eps "
@@ -233,17 +264,27 @@ def main() -> int:
     fit = max(1, int((total * 0.80 - 1.2 * batch_bytes) // batch_bytes))
     n_buf = max(1, min(want, fit))
 
+    if args.probe_distance:
+        return probe_distance(N, d, dev, total, max(1, min(args.steps, 5)))
+
+    # The residuals and the ring of gradient batches are carved from ONE allocation (each at a
+    # multiple of 2 MiB): on this part a stream over two arrays runs 1-1.5 % faster when they
+    # come from one allocation than from separate ones, and how fast depends on the distance
+    # between them (bench.py --probe-distance; up to 7 % between the best and the worst).
     src = wl.GradientSource(cfg, dev)
-    ring = []
+    pitch = (N * d * 4 + (1 << 21) - 1) // (1 << 21) * (1 << 21) // 4
+    slab = torch.empty(n_buf * pitch + N * d, dtype=torch.float32, device=dev)
+    eps = slab[:N * d].view(N, d)
+    eps.zero_()
+    ring = [slab[(b + 1) * pitch:(b + 1) * pitch + N * d].view(N, d) for b in range(n_buf)]
     for b in range(n_buf):
-        ring.append(src.step(b + 1))
+        src.fill(b + 1, ring[b])
     torch.cuda.synchronize()
     checksums = [f"{wl.checksum(t):016x}" for t in ring]      # per (config, step) input batch
 
     side = torch.cuda.Stream(device=dev) if args.graph else None
     ctx = bts.BtsContext(N, d, cfg.K_up, cfg.K_dn, stream=side)
     ctx.set_path({"auto": 0, "dense": 1, "single": 2, "three": 3}[args.path])
-    eps = torch.zeros((N, d), dtype=torch.float32, device=dev)
     delta = torch.zeros(d, dtype=torch.float32, device=dev)
     w = wl.weights0(cfg, dev)
     p = torch.from_numpy(wl.p_weights(cfg)).to(dev)
